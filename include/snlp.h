@@ -168,6 +168,25 @@ int snlp_evaluate_branches(snlp_ctx* ctx, float* g_out, void* stream);
  * probe: NULL or [2, L] as one round of snlp_iterate. */
 int snlp_correction_scan(snlp_ctx* ctx, int mode, const float* g, float* probe, void* stream);
 
+/* For callers that cannot allocate device memory or carve a workspace: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  snlp_correction_scan_static is snlp_correction_scan without a context:
+ * the same kernels, the same strict-fp32 order and the same probe, on caller-owned buffers only --
+ *   trace [L+1, M, n, d] fp32 (slot 0 is read, slots 1..L are written in place), g [L, M, d] fp32,
+ *   Hres [L, n, n] and post [L, n] fp32 (DEVICE pointers here; NULL when n_streams == 1; Hres may be NULL for
+ *   SNLP_IDN), probe NULL or [2, L] fp32 as one round of snlp_iterate.
+ * The probe's per-workgroup partial sums go to a fixed array inside the library (SNLP_STATIC_SCRATCH_BYTES =
+ * 4 MiB of device memory per GPU, held until the process ends) instead of a workspace.  The call allocates nothing
+ * and frees nothing; its only set-up is resolving that array's device address the first time it runs on a GPU
+ * (so make the first call on each GPU outside a stream capture).  Limits: ceil(M * d / 4 / b) * 2 * L <= 2^20
+ * floats with b = 64 when M * d <= 2^20 and 256 otherwise (all five benchmark shapes fit); a shape beyond that
+ * with probe != NULL returns SNLP_E_WORKSPACE and launches nothing (probe = NULL needs no scratch and always fits).
+ * Errors are reported through snlp_last_error(NULL).  All calls on one GPU share the one array: calls that overlap
+ * in time on the same GPU (different streams or threads) race on it and must be serialised by the caller; nothing
+ * in it has to start at zero, every entry that is read is written first by the same call. */
+#define SNLP_STATIC_SCRATCH_BYTES ((size_t)4 << 20)
+int snlp_correction_scan_static(int mode, int L, int M, int n_streams, int d, float* trace, const float* g,
+                                const float* Hres, const float* post, float* probe, void* stream);
+
 /* Diagonal surrogate A_l = diag(a_l) (Methods, "Diagonal Newton (DiagN)"; Appendix "Algorithm", Alg. 3) with the
  * diagonals SUPPLIED by the caller, diag [L, M, d] fp32 (how they are estimated is outside this library).
  * Single-stream models only.  The elementwise affine recurrence of Alg. 3 is walked left to right in strict fp32:

@@ -50,6 +50,7 @@ _SIGNATURES = {
     "snlp_residual_norm": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]),
     "snlp_evaluate_branches": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "snlp_correction_scan": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "snlp_correction_scan_static": (C.c_int, [C.c_int] * 5 + [C.c_void_p] * 6),
     "snlp_correction_scan_diag": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "snlp_iterate_diag": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]),
     "snlp_set_skip_converged": (C.c_int, [C.c_void_p, C.c_int]),
@@ -86,6 +87,21 @@ def load_library():
 
 def _ptr(t: Optional[torch.Tensor]):
     return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def correction_scan_static(mode, trace, g, Hres=None, post=None, probe=None):
+    """snlp_correction_scan_static: the correction scan on caller-owned device tensors, no context and no workspace.
+    trace [L+1, M, n, d], g [L, M, d], Hres [L, n, n] / post [L, n] (device tensors, n > 1), probe [2, L] or None."""
+    lib = load_library()
+    for t in (trace, g, Hres, post, probe):
+        if t is not None and (t.dtype != torch.float32 or not t.is_contiguous() or t.device != trace.device):
+            raise SnlpError("arguments must be contiguous fp32 tensors on one device")
+    L1, M, n, d = trace.shape
+    with torch.cuda.device(trace.device):
+        rc = lib.snlp_correction_scan_static(mode, L1 - 1, M, n, d, _ptr(trace), _ptr(g), _ptr(Hres), _ptr(post), _ptr(probe),
+                                             C.c_void_p(torch.cuda.current_stream(trace.device).cuda_stream))
+    if rc != 0:
+        raise SnlpError("snlp_correction_scan_static: %s (%d)" % (lib.snlp_last_error(None).decode(), rc))
 
 
 class Snlp:

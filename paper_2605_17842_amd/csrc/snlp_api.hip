@@ -7,6 +7,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -652,6 +653,78 @@ int snlp_stage_buffer(snlp_ctx* c, const char* name, void** dev, size_t* bytes) 
       return SNLP_OK;
     }
   return fail(c, SNLP_E_BAD_ARG, std::string("unknown stage buffer: ") + name);
+}
+
+}  // extern "C"
+
+// ------------------------------------------------------------------------------------------------
+// The correction scan for callers that cannot allocate: the probe's per-workgroup partial sums, which the
+// context-based calls keep in the caller's workspace, live in a fixed array in device memory that every GPU
+// the library runs on holds until the process ends.
+namespace {
+
+constexpr size_t kStaticScratchFloats = SNLP_STATIC_SCRATCH_BYTES / sizeof(float);
+static __device__ __align__(256) __attribute__((used)) float snlp_static_scratch[kStaticScratchFloats];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+float* g_scratch_ptr[kMaxDevices] = {};   // device address of the array on each GPU, resolved on first use
+
+// Device address of this GPU's copy of the array (each GPU has its own, at its own address).  In host code the
+// array's name is only a handle for the runtime, never an address a kernel can use.
+int static_scratch(float** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(nullptr, e, "hipGetDevice");
+  if (dev < 0 || dev >= kMaxDevices) return fail(nullptr, SNLP_E_BAD_CONFIG, "device ordinal beyond the static scratch table");
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(snlp_static_scratch));
+    if (e != hipSuccess || !p) return hip_fail(nullptr, e, "hipGetSymbolAddress(static scratch)");
+    g_scratch_ptr[dev] = static_cast<float*>(p);
+  }
+  *out = g_scratch_ptr[dev];
+  return SNLP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int snlp_correction_scan_static(int mode, int L, int M, int n_streams, int d, float* trace, const float* g,
+                                const float* Hres, const float* post, float* probe, void* stream) {
+  snlp_ctx* c = nullptr;   // errors are reported through snlp_last_error(NULL)
+  if (mode != SNLP_IDN && mode != SNLP_HCN) return fail(c, SNLP_E_BAD_ARG, "mode must be SNLP_IDN or SNLP_HCN");
+  if (L < 1 || L > 256) return fail(c, SNLP_E_BAD_CONFIG, "L must be in 1..256");
+  if (M < 1 || d < 4 || d % 4 != 0 || d > 4096) return fail(c, SNLP_E_BAD_CONFIG, "M must be positive, d a multiple of 4 and at most 4096");
+  if (!(n_streams == 1 || n_streams == 2 || n_streams == 3 || n_streams == 4 || n_streams == 8))
+    return fail(c, SNLP_E_BAD_CONFIG, "n_streams must be 1, 2, 3, 4 or 8");
+  if ((long long)M * (d / 4) >= (1ll << 31)) return fail(c, SNLP_E_BAD_CONFIG, "M * d too large");
+  if (mode == SNLP_HCN && n_streams == 1) return fail(c, SNLP_E_BAD_ARG, "SNLP_HCN needs n_streams > 1");
+  if (!trace || !g) return fail(c, SNLP_E_BAD_ARG, "null trace or g");
+  if ((reinterpret_cast<uintptr_t>(trace) & 15) != 0 || (reinterpret_cast<uintptr_t>(g) & 15) != 0)
+    return fail(c, SNLP_E_BAD_ARG, "trace and g must be 16-byte aligned");
+  if (n_streams > 1 && (!post || (mode == SNLP_HCN && !Hres)))
+    return fail(c, SNLP_E_BAD_ARG, "n_streams > 1 needs post (and Hres for SNLP_HCN)");
+  Dims D{};
+  D.L = L; D.d = d; D.n = n_streams; D.M = M; D.B = 1; D.T = M; D.H = 1; D.dh = d; D.F = 0; D.P = 0; D.eps = 0.f;
+  float* partials = nullptr;
+  if (probe) {
+    const size_t need = (size_t)scan_partial_blocks(D) * 2 * (size_t)L;
+    if (need > kStaticScratchFloats)
+      return fail(c, SNLP_E_WORKSPACE, "probe partials of this shape exceed the static scratch (blocks * 2 * L floats > 2^20): "
+                                       "pass probe = NULL or use snlp_correction_scan with a workspace");
+    const int rc = static_scratch(&partials);
+    if (rc) return rc;
+  }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  // every entry of the partials that the final reduction reads is written by the scan of this call, so nothing has to
+  // start at zero
+  SNLP_TRY(launch_scan(s, D, mode, 1, L, trace, g, n_streams > 1 ? Hres : nullptr, n_streams > 1 ? post : nullptr, true,
+                       partials, false), "correction scan (static scratch)");
+  if (probe) SNLP_TRY(launch_probe_finalize(s, D, L, partials, probe, false, 0), "probe finalize (static scratch)");
+  return SNLP_OK;
 }
 
 }  // extern "C"
