@@ -139,10 +139,11 @@ def attention(q: np.ndarray, k: np.ndarray, v: np.ndarray,
     return out
 
 
-def attn_update(model: Model, l: int, u: np.ndarray) -> np.ndarray:
-    """a_l(u) = Attn_l(norm(u)) Wo_l for layer l (1-based) at input u [M, d]; fp64."""
+def qkv_heads(model: Model, l: int, u: np.ndarray) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """q, k, v of layer l (1-based) at input u [M, d], each [B, H, T, dh] (fp64): norm(u) Wqkv split into
+    heads, q and k rotated at positions P + t and then normalised per head."""
     md = model
-    B, T, H, dh, d = md.B, md.T, md.n_heads, md.head_dim, md.d
+    B, T, H, dh = md.B, md.T, md.n_heads, md.head_dim
     u = np.asarray(u, dtype=f64)
     x = rmsnorm(u, md.rms_eps)
     qkv = x @ np.asarray(md.Wqkv[l - 1], dtype=f64)                        # [M, 3d]
@@ -151,11 +152,22 @@ def attn_update(model: Model, l: int, u: np.ndarray) -> np.ndarray:
     cos, sin = rope_cos_sin(md.P + np.arange(T), dh, md.rope_base)
     q = rmsnorm(apply_rope(q, cos, sin), md.rms_eps)
     k = rmsnorm(apply_rope(k, cos, sin), md.rms_eps)
+    return q, k, np.ascontiguousarray(v)
+
+
+def attn_heads(model: Model, l: int, u: np.ndarray) -> np.ndarray:
+    """Attn_l(norm(u)): the heads' outputs of layer l side by side, [M, d] (fp64), before the output projection."""
+    md = model
+    q, k, v = qkv_heads(md, l, u)
     kpre = md.Kpre[l - 1] if md.Kpre is not None else None
     vpre = md.Vpre[l - 1] if md.Vpre is not None else None
-    o = attention(q, k, np.ascontiguousarray(v), kpre, vpre)               # [B, H, T, dh]
-    o = o.transpose(0, 2, 1, 3).reshape(B * T, d)
-    return o @ np.asarray(md.Wo[l - 1], dtype=f64)
+    o = attention(q, k, v, kpre, vpre)                                     # [B, H, T, dh]
+    return o.transpose(0, 2, 1, 3).reshape(md.B * md.T, md.d)
+
+
+def attn_update(model: Model, l: int, u: np.ndarray) -> np.ndarray:
+    """a_l(u) = Attn_l(norm(u)) Wo_l for layer l (1-based) at input u [M, d]; fp64."""
+    return attn_heads(model, l, u) @ np.asarray(model.Wo[l - 1], dtype=f64)
 
 
 def mlp_update(model: Model, l: int, u_mid: np.ndarray) -> np.ndarray:

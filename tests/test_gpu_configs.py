@@ -3,10 +3,10 @@
 Same tolerances as test_gpu_parity.py.  Where a workload asks for K = L, the GPU result after L rounds is
 compared with the oracle's SEQUENTIAL forward: the oracle's own K = L iterate equals its sequential trace
 bit for bit (pinned on small shapes in test_oracle_pins.py), and L oracle rounds at these sizes would take
-minutes.  The d26 long-prefill workload (one oracle round is ~2 minutes of CPU) is checked in full at a
-reduced block length T = 512 for every K = 1..26, and at the full T = 4096 on sampled outputs: the K = 1
-increments h_l - h_{l-1} = g_l(h_0) of sampled layers against the oracle, plus the invariants that hold at
-any size (finite termination bit for bit against the GPU sequential trace, zero residual of converged layers).
+minutes.  The d26 long-prefill workload (one oracle round is ~2 minutes of CPU) is checked at a reduced block
+length T = 512 for every K = 1..26, and at the full T = 4096 against the oracle for K = 1, 2, 3 and the
+sequential forward (every layer), plus the invariants that hold at any size for
+K = 4..26 (finite termination bit for bit against the GPU sequential trace, zero residual of converged layers).
 """
 import json
 import os
@@ -150,34 +150,122 @@ def test_config5_d26_reduced_block_every_K():
     m.close()
 
 
-def test_config5_d26_full_block_sampled():
+# ---- d26 long prefill at its full size (T = 4096) against the oracle: K = 1, 2, 3 and the sequential forward, every
+# layer.  One oracle layer at this size is several seconds of CPU, so the work is cut into steps of
+# at most 13 layer evaluations, one test each, sharing the state below (run in file order; -x stops at the first
+# failure).  The oracle's rounds are composed here from its own pieces exactly as oc.iterate composes them
+# (branch outputs at the previous iterate, residual, correction scan); layers that are already exact are left out
+# of a round, which the oracle pins as bit-identical to full rounds (test_leaving_converged_layers_out_changes_nothing).
+
+@pytest.fixture(scope="module")
+def d26():
     import gpu_helpers as gh
     shp = si.config(5)
     t = si.generate(shp)
-    md = oracle_model(shp, t, widen=False)
-    m = gh.gpu_model(shp, t)
-    gseq = m.sequential_forward(0, m.h0)
+    st = {"shp": shp, "t": t, "md": oracle_model(shp, t, widen=False), "m": gh.gpu_model(shp, t)}
+    m = st["m"]
+    st["gseq"] = m.sequential_forward(0, m.h0)
     m.init_trace(m.h0)
-    probe = torch.zeros((1, 2, shp.L), dtype=torch.float32, device=m.device)
-    m.iterate(0, 1, probe)
-    torch.cuda.synchronize()
-    g1 = m.trace.cpu().numpy()
-    # K = 1 from the h0 initialisation: h_l - h_{l-1} = g_l(h_0); oracle on sampled layers
-    for l in (1, 14, 26):
-        say("d26 full: oracle branch of layer %d at h_0" % l)
-        ref = oc.branch_output(md, l, t["h0"])
-        inc = g1[l][:, 0, :].astype(np.float64) - g1[l - 1][:, 0, :].astype(np.float64)
-        e = rel_err(inc, ref)
-        say("d26 full: K=1 increment of layer %d rel err %.3e" % (l, e))
-        assert e < TOL_BF16
-        # the probe's first-round residual of that layer is ||g_l(h_0)||
-        r = float(np.sqrt(probe[0, 0, l - 1].item()))
-        assert abs(r - np.linalg.norm(ref.astype(np.float64))) <= TOL_BF16 * np.linalg.norm(ref.astype(np.float64))
-    assert np.array_equal(g1[1], gseq[1].cpu().numpy())
-    # full-size sweep on the GPU: invariants that hold at any size, and the per-K report
+    st["probe"] = torch.zeros((3, 2, shp.L), dtype=torch.float32, device=m.device)
+    gk = []
+    for k in range(3):
+        m.iterate(0, 1, st["probe"][k:])
+        torch.cuda.synchronize()
+        gk.append(m.trace.cpu().numpy())
+    st["gpu_K"] = gk                                         # GPU traces after K = 1, 2, 3
+    st["tr"] = [oc.init_trace(st["md"], t["h0"])]            # oracle traces after K = 0, 1, 2
+    st["g"] = {}
+    yield st
+    m.close()
+
+
+def _oracle_branches(st, K, layers):
+    """Branch outputs of round K (1-based) for `layers`, evaluated at the oracle's trace after round K - 1; each is
+    compared at once with the GPU's increment h_l - h_{l-1} of the same round (IDN: the increment IS the branch output)."""
+    md, prev, gpu = st["md"], st["tr"][K - 1], st["gpu_K"][K - 1]
+    for l in layers:
+        t0 = time.time()
+        g = oc.branch_output(md, l, prev[l - 1])
+        st["g"][(K, l)] = g
+        inc = gpu[l][:, 0, :].astype(np.float64) - gpu[l - 1][:, 0, :].astype(np.float64)
+        e = rel_err(inc, g)
+        say("d26 full: round %d layer %2d increment vs oracle branch rel err %.3e (%.1f s)" % (K, l, e, time.time() - t0))
+        assert e < TOL_BF16, (K, l, e)
+
+
+def _oracle_round_done(st, K):
+    """Assemble the oracle's trace after round K from its branch outputs and compare states and probe."""
+    shp, md, prev = st["shp"], st["md"], st["tr"][K - 1]
+    g_all = np.zeros((shp.L, shp.M, shp.d), dtype=np.float32)
+    for l in range(K, shp.L + 1):
+        g_all[l - 1] = st["g"].pop((K, l))
+    r = oc.residual_sq(md, prev, g_all, oc.IDN, S=K - 1)
+    new = oc.correction_scan(md, prev[0], g_all, oc.IDN, S=K - 1, prefix=prev)
+    st["tr"].append(new)
+    err = per_layer_rel_err(st["gpu_K"][K - 1], new)
+    say("d26 full: K=%d max rel err of the states %.3e" % (K, err.max()))
+    assert err.max() < TOL_BF16, err
+    gp = st["probe"][K - 1].cpu().numpy().astype(np.float64)
+    upd = np.sum((new[1:].astype(np.float64) - prev[1:].astype(np.float64)) ** 2, axis=(1, 2, 3))
+    bound = 4 * TOL_BF16 * np.sqrt(max(r.max(), upd.max()))
+    assert np.all(np.abs(np.sqrt(gp[0]) - np.sqrt(r)) <= bound) and np.all(np.abs(np.sqrt(gp[1]) - np.sqrt(upd)) <= bound)
+    assert np.array_equal(gp[0] == 0, r == 0)               # layers exact before the round: zero residual on both sides
+
+
+def test_config5_d26_full_K1_first_half(d26):
+    _oracle_branches(d26, 1, range(1, 14))
+
+
+def test_config5_d26_full_K1_second_half(d26):
+    _oracle_branches(d26, 1, range(14, 27))
+    _oracle_round_done(d26, 1)
+
+
+def test_config5_d26_full_K2_first_half(d26):
+    _oracle_branches(d26, 2, range(2, 14))
+
+
+def test_config5_d26_full_K2_second_half(d26):
+    _oracle_branches(d26, 2, range(14, 27))
+    _oracle_round_done(d26, 2)
+
+
+def test_config5_d26_full_K3(d26):
+    _oracle_branches(d26, 3, range(3, 27))
+    _oracle_round_done(d26, 3)
+
+
+def _oracle_sequential(st, layers):
+    md = st["md"]
+    seq = st["seq"]
+    for l in layers:
+        seq[l] = oc.layer_step(md, l, seq[l - 1], oc.branch_output(md, l, seq[l - 1]), oc.IDN)
+        e = rel_err(st["gseq"][l].cpu().numpy(), seq[l])
+        say("d26 full: sequential layer %2d rel err %.3e" % (l, e))
+        assert e < TOL_BF16, (l, e)
+
+
+def test_config5_d26_full_sequential_first_half(d26):
+    # Alg. 1 in the oracle.  Its first two layers are taken from the oracle's K = 2 trace: after k rounds layers
+    # 1..k ARE the sequential ones, bit for bit (pinned by test_finite_termination_and_prefix_stability_bitwise).
+    d26["seq"] = d26["tr"][2].copy()
+    for l in (1, 2):
+        assert rel_err(d26["gseq"][l].cpu().numpy(), d26["seq"][l]) < TOL_BF16
+    _oracle_sequential(d26, range(3, 15))
+
+
+def test_config5_d26_full_sequential_second_half(d26):
+    _oracle_sequential(d26, range(15, 27))
+
+
+def test_config5_d26_full_sweep_on_gpu(d26):
+    """K = 4..26 at full size on the GPU: the invariants that hold at any size, and the per-K report."""
+    st = d26
+    shp, m, gseq, probe = st["shp"], st["m"], st["gseq"], st["probe"][:1]
+    assert np.array_equal(st["gpu_K"][0][1], gseq[1].cpu().numpy())
     report = []
     seqL = gseq[shp.L].double()
-    for K in range(2, shp.L + 1):
+    for K in range(4, shp.L + 1):
         m.iterate(0, 1, probe)
         torch.cuda.synchronize()
         assert torch.equal(m.trace[: K + 1], gseq[: K + 1]), K
@@ -192,4 +280,3 @@ def test_config5_d26_full_block_sampled():
         os.makedirs(OUT, exist_ok=True)
         with open(os.path.join(OUT, "d26_full_sweep.json"), "w") as fh:
             json.dump(report, fh)
-    m.close()

@@ -80,9 +80,23 @@ def check_iterates(gh, shp, t, mode, Ks, tol, check_seq=True, check_probe=True):
 
 # ------------------------------------------------------------------ correction scan: bit-exact
 
-@pytest.mark.parametrize("n,mode,L,M,d", [(1, oc.IDN, 5, 37, 132), (4, oc.HCN, 6, 19, 260), (4, oc.IDN, 3, 8, 64),
-                                          (2, oc.HCN, 9, 300, 128), (3, oc.HCN, 4, 5, 16), (8, oc.HCN, 3, 7, 32),
-                                          (1, oc.IDN, 26, 64, 1664)])
+# Small batches (M d <= 2^20): one wave per block, operands through the caches -- k_scan<N, U, ., ., 64, false>.
+SCAN_SMALL = [(1, oc.IDN, 5, 37, 132), (4, oc.HCN, 6, 19, 260), (4, oc.IDN, 3, 8, 64), (2, oc.HCN, 9, 300, 128),
+              (3, oc.HCN, 4, 5, 16), (8, oc.HCN, 3, 7, 32), (1, oc.IDN, 26, 64, 1664)]
+# The sizes the prefill workloads run (M d > 2^20: 256-thread blocks with the 4-wave probe reduction; a launch whose
+# trace exceeds 128 MB streams its operands with non-temporal loads).  Template reached, from scan_block_threads and
+# kStreamBytes in the launcher:
+SCAN_PREFILL = [
+    (4, oc.HCN, 20, 2048, 1280),   # d20 HCN workload: 839 MB of trace -> k_scan<4, 2, ., ., 256, true>
+    (1, oc.IDN, 26, 4096, 1664),   # d26 long prefill: 709 MB            -> k_scan<1, 4, ., ., 256, true>
+    (1, oc.IDN, 12, 2048, 768),    # d12 prefill: 75 MB                   -> k_scan<1, 4, ., ., 256, false>
+    (4, oc.HCN, 5, 1024, 1280),    # 105 MB                               -> k_scan<4, 2, ., ., 256, false>
+    (4, oc.IDN, 3, 1024, 1280),    # H = I block on four streams          -> k_scan<4, 2, ., ., 256, false>, mode IDN
+    (2, oc.HCN, 7, 2048, 1280),    # 147 MB                               -> k_scan<2, 2, ., ., 256, true>
+]
+
+
+@pytest.mark.parametrize("n,mode,L,M,d", SCAN_SMALL + SCAN_PREFILL)
 def test_correction_scan_bit_exact_and_probe(gh, n, mode, L, M, d):
     say("scan n=%d mode=%d L=%d M=%d d=%d" % (n, mode, L, M, d))
     rng = np.random.default_rng(100 + n + L)
@@ -278,7 +292,8 @@ def test_prefix_and_fwd_initialisation(gh, bf16, n, S, init):
 
 # ------------------------------------------------------------------ diagonal surrogate with supplied diagonals
 
-@pytest.mark.parametrize("L,M,d", [(5, 37, 132), (26, 64, 1664), (3, 300, 128)])
+@pytest.mark.parametrize("L,M,d", [(5, 37, 132), (26, 64, 1664), (3, 300, 128),
+                                   (12, 2048, 768), (26, 4096, 1664)])   # the last two: prefill sizes, every block full
 def test_diag_correction_scan_bit_exact(gh, L, M, d):
     import paper_2605_17842_amd as snlp
     rng = np.random.default_rng(300 + L)

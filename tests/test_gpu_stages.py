@@ -1,0 +1,82 @@
+"""Stage-by-stage parity of one batched evaluation (Eq. (4)) on the bf16 path against the CPU oracle (-m gpu).
+
+The hidden-state bound of the other parity tests (2e-2 on states that are ~97 % residual stream) cannot see the
+attention kernels; here every stage output -- pre-mixed input, rotated q / k, v, the heads' outputs, the attention
+update a and the MLP update m = g - a -- is compared with the oracle relative to its own norm, token row by token
+row (stage_checks.py states the bound and where it comes from).  Cases cover both attention kernels, the decode
+kernel's own rotation of q and of the block's k rows behind ragged prefixes, prefixes whose values are zero (the
+output is then carried by the block's own keys alone), distinct residual streams, and the d20 workloads at full size.
+"""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import snlp_oracle as oc
+import stage_checks as sc
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print("[case] " + msg, flush=True)
+    sys.stdout.flush()
+
+
+def gpu_stages(m, shp, l):
+    """Stage buffers of layer l (1-based) of the last evaluation, as fp64 arrays shaped like the oracle's."""
+    M, d, H, dh = shp.M, shp.d, shp.n_heads, shp.head_dim
+    def buf(name, width):
+        return m.stage_buffer(name).view(shp.L, M, width)[l - 1].float().cpu().numpy().astype(np.float64)
+    qkv = buf("qkv", 3 * d)
+    a = buf("a", d)
+    g = buf("g", d)
+    out = {"q": qkv[:, :d].reshape(M, H, dh), "k": qkv[:, d:2 * d].reshape(M, H, dh), "v": qkv[:, 2 * d:].reshape(M, H, dh),
+           "attn": buf("attn", d), "a": a, "m": g - a}
+    if shp.n_streams > 1:
+        out["u"] = buf("u", d)
+    return out
+
+
+def check_state(m, case, md, trace_np, label):
+    shp = case.shape
+    m.trace.copy_(torch.from_numpy(trace_np))
+    m.bind_trace(m.trace)
+    m.evaluate_branches()
+    torch.cuda.synchronize()
+    fused_rope = shp.bf16 and shp.head_dim == 128 and shp.T <= 16 and shp.P >= 512
+    tol = sc.tolerances()
+    worst = {}
+    for l in (case.layers or range(1, shp.L + 1)):
+        ref = sc.oracle_stages(md, l, trace_np[l - 1])
+        errs = sc.compare_stages(gpu_stages(m, shp, l), ref, shp.n_streams, rotated_qk=not fused_rope)
+        for k, e in errs.items():
+            worst[k] = max(worst.get(k, 0.0), e)
+            assert e < tol[k], "%s %s layer %d stage %s: row-wise relative error %.3e >= %.0e" % (case.name, label, l, k, e, tol[k])
+    say("%s %s: worst row-wise relative errors %s" % (case.name, label, " ".join("%s=%.2e" % kv for kv in worst.items())))
+
+
+def run_stage_case(case):
+    from paper_2605_17842_amd import harness as gh
+    shp = case.shape
+    t = case.tensors()
+    md = sc.model_of(case, t)
+    m = gh.gpu_model(shp, t)
+    tr0 = oc.init_trace(md, t["h0"])
+    check_state(m, case, md, tr0, "at the h0 initialisation")
+    if case.second_state:
+        mode = oc.HCN if shp.n_streams > 1 else oc.IDN
+        tr1, _, _ = oc.iterate(md, tr0, mode, 1)          # every layer now has its own input
+        check_state(m, case, md, tr1, "at the oracle's K=1 trace")
+    m.close()
+
+
+@pytest.mark.parametrize("case", sc.SMALL_CASES, ids=lambda c: c.name)
+def test_stage_parity_small_cases(case):
+    run_stage_case(case)
+
+
+@pytest.mark.parametrize("case", sc.FULL_CASES, ids=lambda c: c.name)
+def test_stage_parity_d20_workloads(case):
+    run_stage_case(case)

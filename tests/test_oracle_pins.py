@@ -56,6 +56,62 @@ def test_golden_hcn_scan_matches_hand_computation():
     assert np.array_equal(tr[2].ravel(), g["expect_X2"])
 
 
+def _stub_branch(model, l, u):
+    """F(u) = a + m with a = 2 u, m = 0.5 * reverse_channels(u + a) (the stub of hc_sublayer_premix_small.txt)."""
+    u = np.asarray(u, dtype=np.float64)
+    a = 2.0 * u
+    return a, 0.5 * (u + a)[:, ::-1]
+
+
+def _hc_sublayer_fixture_holds(mod) -> bool:
+    """The hand-worked two-layer hyper-connection fixture through mod.premix and mod.sequential_forward, the
+    branch replaced by the fixture's stub."""
+    g = read_golden("hc_sublayer_premix_small.txt")
+    md = mod.Model(L=2, d=2, n_heads=1, head_dim=2, d_mlp=1, B=1, T=1, P=0, Wqkv=[], Wo=[], Wfc=[], Wproj=[],
+                   n_streams=2, Hres=np.stack([g["H1"].reshape(2, 2), g["H2"].reshape(2, 2)]),
+                   pre=np.stack([g["pre1"], g["pre2"]]), post=np.stack([g["post1"], g["post2"]]))
+    X0 = g["X0"].reshape(1, 2, 2)
+    real = mod.branch
+    mod.branch = _stub_branch
+    try:
+        tr = mod.sequential_forward(md, X0, mod.HCN)
+        u1 = mod.premix(md, 1, tr[0])
+        u2 = mod.premix(md, 2, tr[1])
+    finally:
+        mod.branch = real
+    return (np.array_equal(u1.ravel(), g["expect_u1"]) and np.array_equal(u2.ravel(), g["expect_u2"])
+            and np.array_equal(tr[1].ravel(), g["expect_X1"]) and np.array_equal(tr[2].ravel(), g["expect_X2"]))
+
+
+def test_golden_hc_sublayer_with_premix_matches_hand_computation():
+    assert _hc_sublayer_fixture_holds(oc)
+
+
+def test_premix_one_hot_selects_a_stream_and_matches_scalar_loop():
+    """u = sum_j pre[j] X[:, j]: a one-hot pre returns that stream exactly; a general pre equals the scalar loop."""
+    rng = np.random.default_rng(5)
+    L, n, M, d = 3, 4, 5, 6
+    X = rng.standard_normal((M, n, d)).astype(np.float32)              # distinct streams
+    for j in range(n):
+        pre = np.zeros((L, n), np.float32)
+        pre[:, j] = 1.0
+        md = oc.Model(L=L, d=d, n_heads=1, head_dim=d, d_mlp=1, B=M, T=1, P=0, Wqkv=[], Wo=[], Wfc=[], Wproj=[],
+                      n_streams=n, Hres=None, pre=pre, post=np.ones((L, n), np.float32))
+        assert np.array_equal(oc.premix(md, 2, X), X[:, j, :].astype(np.float64))
+    pre = rng.uniform(-1, 1, (L, n)).astype(np.float32)
+    md = oc.Model(L=L, d=d, n_heads=1, head_dim=d, d_mlp=1, B=M, T=1, P=0, Wqkv=[], Wo=[], Wfc=[], Wproj=[],
+                  n_streams=n, Hres=None, pre=pre, post=rng.uniform(-1, 1, (L, n)).astype(np.float32))
+    for l in (1, 3):
+        u = oc.premix(md, l, X)
+        for m in range(M):
+            for c in range(d):
+                want = sum(float(pre[l - 1, j]) * float(X[m, j, c]) for j in range(n))
+                assert abs(u[m, c] - want) < 1e-12
+    # single-stream models: the branch input is the state itself
+    md1 = oc.Model(L=1, d=d, n_heads=1, head_dim=d, d_mlp=1, B=M, T=1, P=0, Wqkv=[], Wo=[], Wfc=[], Wproj=[])
+    assert np.array_equal(oc.premix(md1, 1, X[:, :1, :]), X[:, 0, :].astype(np.float64))
+
+
 def test_golden_idn_prefix_matches_hand_computation():
     g = read_golden("idn_prefix_small.txt")
     md = oc.Model(L=3, d=1, n_heads=1, head_dim=1, d_mlp=1, B=1, T=1, P=0, Wqkv=[], Wo=[], Wfc=[], Wproj=[])
@@ -403,6 +459,8 @@ def _pins_hold(mod) -> bool:
         test_branch_matches_torch_library_composition()
         test_rope_is_complex_rotation_with_half_split_pairs()
         test_one_step_idn_closed_form()
+        if not _hc_sublayer_fixture_holds(mod):
+            return False
         return True
     except AssertionError:
         return False
@@ -443,6 +501,22 @@ def test_pins_catch_planted_mistakes(monkeypatch):
                         lambda model, trace, S=0: np.stack([oc.branch_output(model, l, trace[l]) for l in range(1, model.L + 1)]))
     assert not _pins_hold(oc)
     monkeypatch.setattr(oc, "evaluate_branches", orig_eval)
+    # stream pre-mix weighted by post instead of pre, and with the stream axis reversed
+    orig_premix = oc.premix
+
+    def premix_with(pick):
+        def wrong(model, l, X):
+            X = np.asarray(X, dtype=np.float64)
+            if model.n_streams == 1:
+                return X[:, 0, :]
+            return np.einsum("j,mjc->mc", np.asarray(pick(model, l), dtype=np.float64), X)
+        return wrong
+
+    monkeypatch.setattr(oc, "premix", premix_with(lambda model, l: model.post[l - 1]))
+    assert not _pins_hold(oc)
+    monkeypatch.setattr(oc, "premix", premix_with(lambda model, l: model.pre[l - 1][::-1]))
+    assert not _pins_hold(oc)
+    monkeypatch.setattr(oc, "premix", orig_premix)
     assert _pins_hold(oc)
 
 
