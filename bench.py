@@ -41,8 +41,8 @@ def main():
     ap.add_argument("--block", type=int, default=8, help="new tokens per sequence T (1, 4 or 8)")
     ap.add_argument("--no-extras", action="store_true", help="skip the K curve, the other T values and the prefill GEMM figures")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--all-configs", action="store_true",
-                    help="also time the d26 long-prefill workload in the extras (1.7 GB of weights to generate)")
+    ap.add_argument("--skip-d26", action="store_true",
+                    help="leave the d26 long-prefill workload out of the extras (1.7 GB of weights to generate)")
     ap.add_argument("--prefill-only", action="store_true",
                     help="run only the d20 HCN prefill section (M = 2048) and print its figures: for profiling the MFMA GEMMs")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -107,8 +107,11 @@ def main():
             "stage_us": st4,
             "gemm_TFLOPs": {k: v / (st4[k] * 1e-6) / 1e12 for k, v in fl.items()},
             "gemm_mfma_frac": {k: v / (st4[k] * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS for k, v in fl.items()},
-            "scan_GBs": (8.0 + 8.0 * shp4.n_streams - 4.0) * d4 * L4 * M4 / (st4["correction_scan"] * 1e-6) / 1e9,
+            # the timed rounds pass no probe: the scan reads g (4 d bytes per layer-token) and writes the n streams
+            # of the new state (4 n d); with a probe it also reads the old state ((4 + 8 n) d in all)
+            "scan_GBs": (4.0 + 4.0 * shp4.n_streams) * d4 * L4 * M4 / (st4["correction_scan"] * 1e-6) / 1e9,
         }
+        res["scan_frac_of_hbm_peak"] = res["scan_GBs"] / HBM_PEAK_GBS
         m4.close()
         del m4, t4, seq4
         torch.cuda.empty_cache()
@@ -159,6 +162,27 @@ def main():
              "iteration_hbm_floor_us": iter_bytes / (HBM_PEAK_GBS * 1e9) * 1e6,
              "iteration_frac_of_hbm_floor": (iter_bytes / (HBM_PEAK_GBS * 1e9)) / t_iter}
 
+    def event_times_us(fn, warm, runs):
+        """Per-call durations from events recorded on the launch stream between consecutive calls (the queue stays
+        full; no synchronisation inside the series)."""
+        for _ in range(warm):
+            fn()
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(runs + 1)]
+        sync()
+        evs[0].record()
+        for i in range(runs):
+            fn()
+            evs[i + 1].record()
+        sync()
+        return np.array([evs[i].elapsed_time(evs[i + 1]) * 1e3 for i in range(runs)])
+
+    def percentiles(x):
+        return {"median_us": float(np.median(x)), "p10_us": float(np.percentile(x, 10)), "p90_us": float(np.percentile(x, 90)),
+                "mean_us": float(np.mean(x)), "runs": int(len(x))}
+
+    # the paper's timing protocol (Experiments, setup: 50 warm-up runs, 200 measured runs), per-step event times
+    extra["iteration_us_50warmup_200runs"] = percentiles(event_times_us(step, 50, 200))
+
     if not args.no_extras:
         # per-stage breakdown of one iteration (all stages carry events: slightly slower than t_iter)
         m.profile_stages((1 << snlp.N_STAGES) - 1)
@@ -173,6 +197,8 @@ def main():
         extra["weight_streaming_GBs"] = {k: v / (extra["stage_us"][k] * 1e-6) / 1e9 for k, v in gemm_bytes.items()}
         scan_bytes = 12.0 * d * L * M      # read g and the old trace, write the new trace
         extra["scan_GBs"] = scan_bytes / (extra["stage_us"]["correction_scan"] * 1e-6) / 1e9
+        extra["scan_frac_of_hbm_peak"] = extra["scan_GBs"] / HBM_PEAK_GBS
+        extra["weight_streaming_frac_of_hbm_peak"] = {k: v / HBM_PEAK_GBS for k, v in extra["weight_streaming_GBs"].items()}
 
         # sequential forward with the same kernels, and the speed-versus-K curve
         seq_out = torch.empty_like(m.trace)
@@ -180,6 +206,10 @@ def main():
             m.sequential_forward(snlp.IDN, m.h0, seq_out)
         t_seq = timed(lambda: m.sequential_forward(snlp.IDN, m.h0, seq_out), max(10, args.steps // 10), sync)
         extra["sequential_forward_us"] = t_seq * 1e6
+        extra["sequential_forward_us_50warmup_200runs"] = percentiles(
+            event_times_us(lambda: m.sequential_forward(snlp.IDN, m.h0, seq_out), 50, 200))
+        # the sequential forward moves the same bytes as one iteration (weights, KV prefix, block q/k/v/out)
+        extra["sequential_frac_of_hbm_floor"] = (iter_bytes / (HBM_PEAK_GBS * 1e9)) / t_seq
         # the sequential path stage by stage: average of one layer's launch (event-timed: a few us of timer overhead each)
         m.profile_stages((1 << snlp.N_STAGES) - 1)
         m.profile_read()
@@ -306,9 +336,58 @@ def main():
                         ssd["estimated_speedup"]["K=%d B=%d alpha=%.2f" % (Kd, Bd, alpha)] = est
             extra["self_speculative_estimate"] = ssd
 
+        # The drafting loop itself, timed (no acceptance: that needs trained weights): one round = B one-token SNLP
+        # drafts (h0 initialisation + K rounds at T = 1) followed by ONE sequential forward of the target model over the
+        # B + 1 drafted positions; the KV prefix stays at P rows (growing it is outside this path).  Its cost in units
+        # of one autoregressive step of the target model (sequential forward at T = 1) is what the closed form writes
+        # as B / s + 1.
+        shp1 = shp.with_(T=1)
+        t1 = dict(t)
+        t1["h0"] = si.generate_h0(shp1)
+        m1 = gh.gpu_model(shp1, t1)
+        so1 = torch.empty_like(m1.trace)
+        m1.sequential_forward(snlp.IDN, m1.h0, so1)
+        t_ar = timed(lambda: m1.sequential_forward(snlp.IDN, m1.h0, so1), 20, sync)
+        loop = {"autoregressive_step_us": t_ar * 1e6, "rounds": {}}
+        for Bd in (4, 8):
+            shpv = shp.with_(T=Bd + 1)
+            tv = dict(t)
+            tv["h0"] = si.generate_h0(shpv)
+            mv = gh.gpu_model(shpv, tv)
+            sov = torch.empty_like(mv.trace)
+            mv.sequential_forward(snlp.IDN, mv.h0, sov)
+            t_verify = timed(lambda: mv.sequential_forward(snlp.IDN, mv.h0, sov), 10, sync)
+            for Kd in (1, 2):
+                def draft(Kd=Kd):
+                    m1.init_trace(m1.h0)
+                    m1.iterate(snlp.IDN, Kd, None)
+                draft()
+                t_draft = timed(draft, 50, sync)
+                def one_round(Kd=Kd, Bd=Bd):
+                    for _ in range(Bd):
+                        draft(Kd)
+                    mv.sequential_forward(snlp.IDN, mv.h0, sov)
+                one_round()
+                t_round = timed(one_round, 10, sync)
+                s_meas = t_ar / t_draft
+                row = {"draft_us": t_draft * 1e6, "verify_us": t_verify * 1e6, "round_us": t_round * 1e6,
+                       "drafter_speedup_s": s_meas, "round_cost_closed_form": Bd / s_meas + 1.0,
+                       "round_cost_measured": t_round / t_ar, "estimated_speedup": {}}
+                for alpha in (0.6, 0.8, 0.9, 0.95):
+                    tokens = (1.0 - alpha ** (Bd + 1)) / (1.0 - alpha)
+                    row["estimated_speedup"]["alpha=%.2f" % alpha] = {
+                        "closed_form": tokens / row["round_cost_closed_form"], "with_measured_round": tokens / row["round_cost_measured"]}
+                loop["rounds"]["K=%d B=%d" % (Kd, Bd)] = row
+            mv.close()
+            del mv, sov
+        m1.close()
+        del m1, so1
+        torch.cuda.empty_cache()
+        extra["self_speculative_drafting_loop"] = loop
+
         extra["d20_hcn_prefill"] = prefill_section(4)
         extra["d12_prefill"] = prefill_section(2)
-        if args.all_configs:
+        if not args.skip_d26:
             extra["d26_long_prefill"] = prefill_section(5)
     else:
         m.close()
@@ -331,6 +410,38 @@ def main():
             cores = os.cpu_count()
         cpu = {"value": dt / Kc * 1e6, "unit": "us", "cores": int(cores), "kind": "oracle",
                "sample": "%d IDN iterations of the whole workload (all %d layers), %.1f s in total; value = mean per iteration" % (Kc, L, dt)}
+        if not args.no_extras:
+            # the oracle on every workload: sequential forward and one iteration (both surrogates on the 4-stream
+            # workload), on the first `sample` layers of the workload (each layer has its own seeded stream, so they
+            # are the workload's own first layers), scaled to all L layers
+            del md, tr0
+            per = {}
+            for idx, sample in ((1, 4), (2, 12), (3, 20), (4, 5), (5, 2)):
+                full = si.config(idx)
+                shp_c = si.config(idx, L=sample)
+                if args.skip_d26 and idx == 5:
+                    continue
+                t_c = si.generate(shp_c)
+                md_c = oracle_model(shp_c, t_c)
+                scale = full.L / float(sample)
+                reps = 20 if idx == 1 else 1
+                row = {"cores": int(cores), "sample": "first %d of %d layers, scaled by %.2f" % (sample, full.L, scale)}
+                t0 = time.perf_counter()
+                for _ in range(reps):
+                    oc.sequential_forward(md_c, t_c["h0"], oc.IDN)
+                row["sequential_forward_us"] = (time.perf_counter() - t0) / reps * scale * 1e6
+                tr_c = oc.init_trace(md_c, t_c["h0"])
+                t0 = time.perf_counter()
+                for _ in range(reps):
+                    oc.iterate(md_c, tr_c, oc.IDN, 1)
+                row["idn_iteration_us"] = (time.perf_counter() - t0) / reps * scale * 1e6
+                if full.n_streams > 1:
+                    t0 = time.perf_counter()
+                    oc.iterate(md_c, tr_c, oc.HCN, 1)
+                    row["hcn_iteration_us"] = (time.perf_counter() - t0) * scale * 1e6
+                per[full.name] = row
+                del t_c, md_c, tr_c
+            extra["cpu_oracle_all_workloads"] = per
 
     out = {
         "metric": "snlp_iter_latency_us", "value": t_iter * 1e6, "unit": "us", "n_gpus": 1,
@@ -341,7 +452,26 @@ def main():
                    "L": L, "d": d, "B": B, "T": T, "P": P, "mode": "IDN"},
         "roofline": roof, "cpu_baseline": cpu, "extra": extra,
     }
+    check_rates(out)
     print(json.dumps(out), flush=True)
+
+
+def check_rates(node, path=""):
+    """No reported bandwidth may exceed the HBM peak and no fraction of a peak may exceed 1: such a figure is a wrong
+    byte or flop count, not a measurement."""
+    if isinstance(node, dict):
+        for k, v in node.items():
+            here = path + "/" + str(k)
+            if isinstance(v, (dict, list)):
+                check_rates(v, here)
+            elif isinstance(v, (int, float)):
+                if "GBs" in str(k) or "GBs" in path.rsplit("/", 1)[-1] or (k == "achieved" and node.get("unit") == "GB/s"):
+                    assert v <= HBM_PEAK_GBS, "%s = %.1f GB/s exceeds the HBM peak" % (here, v)
+                if "frac" in str(k) or "frac" in path.rsplit("/", 1)[-1]:
+                    assert v <= 1.0, "%s = %.3f exceeds 1" % (here, v)
+    elif isinstance(node, list):
+        for i, v in enumerate(node):
+            check_rates(v, "%s[%d]" % (path, i))
 
 
 if __name__ == "__main__":
