@@ -91,6 +91,9 @@ SMALL_CASES = [
     StageCase("decode_P999_T16", small("decode_P999_T16", B=1, T=16, P=999, seed=907)),              # P mod 32 = 7: block rows straddle two tiles
     StageCase("decode_P999_T16_v0", small("decode_P999_T16_v0", B=1, T=16, P=999, seed=907), zero_vpre=True),
     StageCase("decode_P2048_T8_v0", small("decode_P2048_T8_v0", T=8, P=2048, seed=908), zero_vpre=True),
+    # 81 key tiles, the last one made of block rows 1..15 only: query row 0 sees none of its keys
+    StageCase("decode_P2559_T16", small("decode_P2559_T16", B=1, T=16, P=2559, seed=910)),
+    StageCase("decode_P2559_T16_v0", small("decode_P2559_T16_v0", B=1, T=16, P=2559, seed=910), zero_vpre=True),
     StageCase("hcn_n4_T33", small("hcn_n4_T33", T=33, n_streams=4, L=3, seed=909), distinct_streams=True),
 ]
 
