@@ -97,7 +97,11 @@ int snlp_bind_kv_prefix(snlp_ctx* ctx, const void* Kpre, const void* Vpre);
  * Needed iff n_streams > 1. */
 int snlp_set_hc(snlp_ctx* ctx, const float* Hres, const float* pre, const float* post);
 
-/* The trace [L+1, M, n, d] fp32; slot 0 is h_0 and is never written by snlp_iterate. */
+/* The trace [L+1, M, n, d] fp32; slot 0 is h_0 and is never written by snlp_iterate.
+ * The library keeps data derived from the bound trace between calls (for large batches the correction leaves the
+ * normalised branch inputs of the next round in the workspace; with snlp_set_skip_converged the count of exact layers).
+ * A caller who writes into the bound trace itself must therefore bind it again (or call snlp_init_trace(_ex)) before
+ * the next call that reads it. */
 int snlp_bind_trace(snlp_ctx* ctx, float* trace);
 
 /* Alg. 2 up to the solver loop.  snlp_set_prefix: the first S layers (0 <= S < L, default 0) are evaluated
@@ -199,7 +203,8 @@ int snlp_iterate_diag(snlp_ctx* ctx, int K, const float* diag, float* probe, voi
 
 /* Diagnostic: device address and byte size of a stage buffer of the last evaluation
  * ("xhat", "qkv", "attn", "a", "xhat2", "hmid", "g", "u").  Layout [L, M, width], element type per dtype
- * ("a", "g", "u" always fp32). */
+ * ("a", "g", "u" always fp32).  After a correction on a large batch "xhat" and "u" already hold the inputs of the
+ * NEXT evaluation (see snlp_bind_trace); after snlp_evaluate_branches / snlp_residual_norm they are the evaluation's own. */
 int snlp_stage_buffer(snlp_ctx* ctx, const char* name, void** dev, size_t* bytes);
 
 /* Measurement aid: per-stage timing with HIP events recorded on the caller's stream around the stage's

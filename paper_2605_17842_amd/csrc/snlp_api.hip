@@ -4,6 +4,7 @@
 #include "../../include/snlp.h"
 #include "snlp_kernels.hpp"
 
+#include <climits>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -58,6 +59,13 @@ struct snlp_ctx {
     if (exact < units()) ++exact;
   }
 
+  // The normalised branch inputs (stage buffers xhat, and u on n-stream models) of layers >= xhat_from are those of the
+  // bound trace as it stands: the correction kernel for large batches leaves them behind for the next round, which
+  // then runs the stand-alone norm pass only for the layers before that (INT_MAX: nothing known).
+  int xhat_from = INT_MAX;
+  void forget_xhat() { xhat_from = INT_MAX; }
+  bool fuses_norm() const { return Fz == 1 && scan_fuses_norm(D); }
+
   int units() const { return D.L / Fz; }
   float* gbuf() const { return reinterpret_cast<float*>(ws + (Fz > 1 ? off_a : off_g)); }   // per-unit branch outputs
 
@@ -108,7 +116,8 @@ void carve(snlp_ctx* c) {
   c->off_hmid = take(L * M * F * c->esz);
   c->off_g = take(L * M * d * sizeof(float));
   c->off_u = take(L * M * d * sizeof(float));   // pre-mixed input (n > 1) or summed attention updates of fused chunks
-  c->off_partials = take((size_t)scan_partial_blocks(D) * 2 * L * sizeof(float));
+  const size_t pblocks = scan_fuses_norm(D) && scan_norm_blocks(D) > scan_partial_blocks(D) ? scan_norm_blocks(D) : scan_partial_blocks(D);
+  c->off_partials = take(pblocks * 2 * L * sizeof(float));
   c->off_probe = take(2 * L * sizeof(float));
   c->ws_bytes = o;
 }
@@ -154,7 +163,7 @@ struct StageTimer {
 
 // Step (1) of the iteration for layers l0..l0+Lc-1 (1-based) reading slot l-1 of `trace`: leaves
 // g_l = a_l + m_l in the g stage buffer.
-int evaluate_layers(snlp_ctx* c, int l0, int Lc, const float* trace, hipStream_t s) {
+int evaluate_layers(snlp_ctx* c, int l0, int Lc, const float* trace, hipStream_t s, int valid_from) {
   const Dims& D = c->D;
   const size_t M = D.M, d = D.d, F = D.F;
   const size_t lo = (size_t)(l0 - 1);
@@ -169,8 +178,10 @@ int evaluate_layers(snlp_ctx* c, int l0, int Lc, const float* trace, hipStream_t
   float* g = c->at<float>(c->off_g);
   float* u = c->at<float>(c->off_u);
 
-  { StageTimer tm(c, 0, s);
-  SNLP_TRY(launch_premix_rmsnorm(s, D, l0, Lc, trace, c->at<float>(c->off_pre), u, xhat, bf), "premix_rmsnorm"); }
+  // layers from valid_from on already have their (pre-mixed and) normalised input in the stage buffers
+  const int npre = valid_from <= l0 ? 0 : (valid_from - l0 < Lc ? valid_from - l0 : Lc);
+  if (npre > 0) { StageTimer tm(c, 0, s);
+  SNLP_TRY(launch_premix_rmsnorm(s, D, l0, npre, trace, c->at<float>(c->off_pre), u, xhat, bf), "premix_rmsnorm"); }
   { StageTimer tm(c, 1, s);
   if (bf) {
     SNLP_TRY(launch_gemm_bf16(s, Lc, D.M, 3 * D.d, D.d, (const bf16_t*)(xhat + lo * M * d * e), M * d,
@@ -312,20 +323,49 @@ int evaluate_fused(snlp_ctx* c, int c0, int Nc, const float* trace, hipStream_t 
 }
 
 // Units are layers, or fused chunks when Fz > 1.
-int evaluate(snlp_ctx* c, int u0, int Uc, const float* trace, hipStream_t s) {
-  return c->Fz > 1 ? evaluate_fused(c, u0, Uc, trace, s) : evaluate_layers(c, u0, Uc, trace, s);
+int evaluate(snlp_ctx* c, int u0, int Uc, const float* trace, hipStream_t s, int valid_from = INT_MAX) {
+  return c->Fz > 1 ? evaluate_fused(c, u0, Uc, trace, s) : evaluate_layers(c, u0, Uc, trace, s, valid_from);
 }
 
+// Evaluation on the bound trace: uses, and afterwards records, which layers' normalised inputs are current.
+int evaluate_bound(snlp_ctx* c, int u0, int Uc, hipStream_t s) {
+  if (c->Fz > 1) { c->forget_xhat(); return evaluate_fused(c, u0, Uc, c->trace, s); }
+  const int rc = evaluate_layers(c, u0, Uc, c->trace, s, c->xhat_from);
+  if (rc == SNLP_OK && u0 + Uc - 1 >= c->D.L && c->xhat_from > u0) c->xhat_from = u0;   // the norm pass filled u0 .. xhat_from - 1
+  return rc;
+}
+
+// fuse_norm: the correction also leaves the next evaluation's normalised inputs of layers l0 + 1 .. L in the stage
+// buffers (large batches only; the caller keeps the bookkeeping).  Returns through *fused whether it did.
 int correct(snlp_ctx* c, int mode, int l0, int Lc, float* trace, const float* g, bool write, float* probe_out,
-            bool sqrt_first, hipStream_t s, bool independent = false) {
+            bool sqrt_first, hipStream_t s, bool independent = false, bool fuse_norm = false, bool* fused = nullptr) {
   const Dims& D = c->D;
   float* partials = (probe_out || !write) ? c->at<float>(c->off_partials) : nullptr;
   const float* H = D.n > 1 ? c->at<float>(c->off_H) : nullptr;
   const float* post = D.n > 1 ? c->at<float>(c->off_post) : nullptr;
+  const bool fuse = fuse_norm && write && !independent && c->fuses_norm();
+  if (fused) *fused = fuse;
   StageTimer tm(c, 8, s);
+  if (fuse) {
+    SNLP_TRY(launch_scan_norm(s, D, mode, l0, Lc, trace, g, H, post, c->at<float>(c->off_pre), c->at<float>(c->off_u),
+                              c->ws + c->off_xhat, c->bf16, partials), "correction scan + next inputs");
+    if (probe_out) SNLP_TRY(launch_probe_finalize(s, D, Lc, partials, probe_out, sqrt_first, l0 - 1, scan_norm_blocks(D)), "probe finalize");
+    return SNLP_OK;
+  }
   SNLP_TRY(launch_scan(s, D, mode, l0, Lc, trace, g, H, post, write, partials, independent), "correction scan");
   if (probe_out) SNLP_TRY(launch_probe_finalize(s, D, Lc, partials, probe_out, sqrt_first, l0 - 1), "probe finalize");
   return SNLP_OK;
+}
+
+// One round's correction on the bound trace with the bookkeeping of the stage buffers.
+int correct_bound(snlp_ctx* c, int mode, int l0, int Lc, const float* g, float* probe_out, hipStream_t s) {
+  bool fused = false;
+  const int rc = correct(c, mode, l0, Lc, c->trace, g, true, probe_out, false, s, false, true, &fused);
+  if (rc != SNLP_OK) { c->forget_xhat(); return rc; }
+  // fused: layers l0 + 1 .. L are fresh and whatever was current up to l0 still is (their input slots did not change)
+  if (fused) { if (c->xhat_from > l0 + 1) c->xhat_from = l0 + 1; }
+  else c->forget_xhat();
+  return rc;
 }
 
 }  // namespace
@@ -403,6 +443,7 @@ int snlp_bind_workspace(snlp_ctx* c, void* dev, size_t bytes) {
   c->ws = static_cast<char*>(dev);
   c->weights_bound = false;
   c->hc_set = false;
+  c->forget_xhat();
   // rotary table for positions P .. P+T-1: angle = pos * base^(-2c/dh), c = 0..dh/2-1, evaluated in fp64
   const Dims& D = c->D;
   const int half = D.dh / 2;
@@ -454,6 +495,7 @@ int snlp_set_hc(snlp_ctx* c, const float* Hres, const float* pre, const float* p
   if (!Hres || !pre || !post) return fail(c, SNLP_E_BAD_ARG, "null hyper-connection parameter");
   if (!c->ws) return fail(c, SNLP_E_NOT_BOUND, "bind the workspace before snlp_set_hc");
   c->forget_exact();
+  c->forget_xhat();
   const size_t L = c->D.L, n = c->D.n;
   SNLP_TRY(hipMemcpy(c->ws + c->off_H, Hres, L * n * n * sizeof(float), hipMemcpyHostToDevice), "copy Hres");
   SNLP_TRY(hipMemcpy(c->ws + c->off_pre, pre, L * n * sizeof(float), hipMemcpyHostToDevice), "copy pre");
@@ -468,6 +510,7 @@ int snlp_bind_trace(snlp_ctx* c, float* trace) {
   if ((reinterpret_cast<uintptr_t>(trace) & 15) != 0) return fail(c, SNLP_E_BAD_ARG, "trace must be 16-byte aligned");
   c->trace = trace;
   c->forget_exact();
+  c->forget_xhat();
   return SNLP_OK;
 }
 
@@ -476,6 +519,7 @@ int snlp_set_prefix(snlp_ctx* c, int S) {
   if (S < 0 || S >= c->units()) return fail(c, SNLP_E_BAD_ARG, "prefix length must satisfy 0 <= S < L (chunks when fused)");
   c->S = S;
   c->forget_exact();
+  c->forget_xhat();
   return SNLP_OK;
 }
 
@@ -492,6 +536,7 @@ int snlp_set_fusion(snlp_ctx* c, int F) {
   c->Fz = F;
   c->S = 0;
   c->forget_exact();
+  c->forget_xhat();
   return SNLP_OK;
 }
 
@@ -505,6 +550,7 @@ int snlp_init_trace_ex(snlp_ctx* c, int mode, int init, const float* h0, void* s
   const int S = c->S;
   int rc;
   c->forget_exact();
+  c->forget_xhat();
   if (S > 0 || init == SNLP_INIT_FWD) {
     if ((rc = check_ready(c, true))) return rc;
     if ((rc = check_mode(c, mode))) return rc;
@@ -539,10 +585,8 @@ int snlp_iterate(snlp_ctx* c, int mode, int K, float* probe, void* stream) {
   const int L = c->units();
   for (int k = 0; k < K; ++k) {
     const int u0 = c->first_unit(mode);
-    if ((rc = evaluate(c, u0, L - u0 + 1, c->trace, s))) return rc;
-    if ((rc = correct(c, mode, u0, L - u0 + 1, c->trace, c->gbuf(), true,
-                      probe ? probe + (size_t)k * 2 * L : nullptr, false, s)))
-      return rc;
+    if ((rc = evaluate_bound(c, u0, L - u0 + 1, s))) return rc;
+    if ((rc = correct_bound(c, mode, u0, L - u0 + 1, c->gbuf(), probe ? probe + (size_t)k * 2 * L : nullptr, s))) return rc;
     c->round_done(mode);
   }
   return SNLP_OK;
@@ -557,9 +601,13 @@ int snlp_sequential_forward(snlp_ctx* c, int mode, const float* h0, float* trace
   const Dims& D = c->D;
   if (h0 != trace_out)
     SNLP_TRY(hipMemcpyAsync(trace_out, h0, (size_t)D.M * D.n * D.d * sizeof(float), hipMemcpyDeviceToDevice, s), "copy h0");
+  c->forget_xhat();   // the stage buffers are about to hold trace_out's inputs, not the bound trace's
+  int valid_from = INT_MAX;
   for (int l = 1; l <= c->units(); ++l) {
-    if ((rc = evaluate(c, l, 1, trace_out, s))) return rc;
-    if ((rc = correct(c, mode, l, 1, trace_out, c->gbuf(), true, nullptr, false, s))) return rc;
+    if ((rc = evaluate(c, l, 1, trace_out, s, valid_from))) return rc;
+    bool fused = false;
+    if ((rc = correct(c, mode, l, 1, trace_out, c->gbuf(), true, nullptr, false, s, false, true, &fused))) return rc;
+    valid_from = fused ? l + 1 : INT_MAX;   // the step left layer l + 1's normalised input behind
   }
   return SNLP_OK;
 }
@@ -570,7 +618,7 @@ int snlp_residual_norm(snlp_ctx* c, int mode, float* out, void* stream) {
   if ((rc = check_mode(c, mode))) return rc;
   if (!out) return fail(c, SNLP_E_BAD_ARG, "null output");
   hipStream_t s = static_cast<hipStream_t>(stream);
-  if ((rc = evaluate(c, c->S + 1, c->units() - c->S, c->trace, s))) return rc;
+  if ((rc = evaluate_bound(c, c->S + 1, c->units() - c->S, s))) return rc;
   return correct(c, mode, c->S + 1, c->units() - c->S, c->trace, c->gbuf(), false, out, true, s);
 }
 
@@ -579,7 +627,7 @@ int snlp_evaluate_branches(snlp_ctx* c, float* g_out, void* stream) {
   if (rc) return rc;
   if (!g_out) return fail(c, SNLP_E_BAD_ARG, "null output");
   hipStream_t s = static_cast<hipStream_t>(stream);
-  if ((rc = evaluate(c, c->S + 1, c->units() - c->S, c->trace, s))) return rc;
+  if ((rc = evaluate_bound(c, c->S + 1, c->units() - c->S, s))) return rc;
   const Dims& D = c->D;
   SNLP_TRY(hipMemcpyAsync(g_out, c->gbuf(), (size_t)c->units() * D.M * D.d * sizeof(float), hipMemcpyDeviceToDevice, s),
            "copy g");
@@ -595,7 +643,7 @@ int snlp_correction_scan(snlp_ctx* c, int mode, const float* g, float* probe, vo
   if (rc) return rc;
   if (!g) return fail(c, SNLP_E_BAD_ARG, "null g");
   c->forget_exact();   // caller-supplied branch outputs: nothing is known about the result
-  return correct(c, mode, c->S + 1, c->units() - c->S, c->trace, g, true, probe, false, static_cast<hipStream_t>(stream));
+  return correct_bound(c, mode, c->S + 1, c->units() - c->S, g, probe, static_cast<hipStream_t>(stream));
 }
 
 namespace {
@@ -617,6 +665,7 @@ int snlp_correction_scan_diag(snlp_ctx* c, const float* g, const float* diag, fl
   if (c->D.n != 1) return fail(c, SNLP_E_BAD_ARG, "the diagonal surrogate is built for single-stream models");
   if (!g || !diag) return fail(c, SNLP_E_BAD_ARG, "null g or diag");
   c->forget_exact();
+  c->forget_xhat();
   return correct_diag(c, c->S + 1, g, diag, probe, static_cast<hipStream_t>(stream));
 }
 
@@ -628,7 +677,8 @@ int snlp_iterate_diag(snlp_ctx* c, int K, const float* diag, float* probe, void*
   hipStream_t s = static_cast<hipStream_t>(stream);
   for (int k = 0; k < K; ++k) {
     const int u0 = c->first_unit(SNLP_IDN);
-    if ((rc = evaluate(c, u0, c->units() - u0 + 1, c->trace, s))) return rc;
+    if ((rc = evaluate_bound(c, u0, c->units() - u0 + 1, s))) return rc;
+    c->forget_xhat();   // the diagonal correction does not prepare the next round's inputs
     if ((rc = correct_diag(c, u0, c->gbuf(), diag, probe ? probe + (size_t)k * 2 * c->units() : nullptr, s))) return rc;
     c->round_done(SNLP_IDN);
   }

@@ -104,49 +104,58 @@ static inline int row_block_threads(int d) {
 constexpr int kMaxVec = 4;   // float4 per thread per row (blocks of 64..1024 threads cover d / 4 in at most 4 passes)
 
 // ------------------------------------------------------------------------------------------------
-// x = rmsnorm(u), u = sum_j pre[j] X[j]  (H^pre of the HC sublayer; n = 1: u = X)
-template <typename OutT, bool STREAM>
+// Branch input of a layer from the n streams of its input state: u = sum_j pre[j] X[j] (H^pre of the HC sublayer),
+// pre[0] * X[0] first, then one fused multiply-add per further stream.  Written once: the stand-alone norm kernel and
+// the correction kernel that also prepares the next round's inputs must produce the same bits.
+template <int N>
+__device__ __forceinline__ float4 premix4(const float4 (&x)[N], const float* __restrict__ pre) {
+  float4 u = x[0];
+  if (N > 1) {
+    const float w0 = pre[0];
+    u.x *= w0; u.y *= w0; u.z *= w0; u.w *= w0;
+#pragma unroll
+    for (int j = 1; j < N; ++j) {
+      const float w = pre[j];
+      u.x = fmaf(w, x[j].x, u.x); u.y = fmaf(w, x[j].y, u.y); u.z = fmaf(w, x[j].z, u.z); u.w = fmaf(w, x[j].w, u.w);
+    }
+  }
+  return u;
+}
+// (x^2 + y^2) + (z^2 + w^2), every operation rounded once
+__device__ __forceinline__ float sumsq4(const float4 u) {
+#pragma clang fp contract(off)
+  return (u.x * u.x + u.y * u.y) + (u.z * u.z + u.w * u.w);
+}
+__device__ __forceinline__ float inv_rms(float ss, int d, float eps) { return 1.0f / sqrtf(ss / (float)d + eps); }
+
+// x = rmsnorm(u), u = sum_j pre[j] X[j]  (n = 1: u = X)
+template <int N, typename OutT, bool STREAM>
 __global__ __launch_bounds__(1024) void k_premix_rmsnorm(const float* __restrict__ trace,
                                                               const float* __restrict__ pre,
                                                               float* __restrict__ ubuf, OutT* __restrict__ xhat,
-                                                              int l0, int M, int n, int d, float eps) {
+                                                              int l0, int M, int d, float eps) {
   __shared__ float sh[kMaxWaves];
   const int row = blockIdx.x;
   const int l = l0 + blockIdx.y;   // 1-based layer; its input is slot l-1
-  const float* in = trace + ((size_t)(l - 1) * M + row) * (size_t)n * d;
+  const float* in = trace + ((size_t)(l - 1) * M + row) * (size_t)N * d;
   const size_t orow = ((size_t)(l - 1) * M + row) * (size_t)d;
   const int nv = d >> 2;
-  float4 v[kMaxVec];
+  const int c4 = threadIdx.x;      // one float4 per thread: the block covers the row (d <= 4096)
+  float4 u = make_float4(0.f, 0.f, 0.f, 0.f);
   float ss = 0.f;
+  if (c4 < nv) {
+    float4 x[N];
 #pragma unroll
-  for (int it = 0; it < kMaxVec; ++it) {
-    const int c4 = threadIdx.x + it * (int)blockDim.x;
-    if (c4 < nv) {
-      float4 u = load4_sel<STREAM>(in + (size_t)c4 * 4);
-      if (n > 1) {
-        const float w0 = pre[(l - 1) * n];
-        u.x *= w0; u.y *= w0; u.z *= w0; u.w *= w0;
-        for (int j = 1; j < n; ++j) {
-          const float w = pre[(l - 1) * n + j];
-          const float4 x = load4_sel<STREAM>(in + (size_t)j * d + (size_t)c4 * 4);
-          u.x = fmaf(w, x.x, u.x); u.y = fmaf(w, x.y, u.y); u.z = fmaf(w, x.z, u.z); u.w = fmaf(w, x.w, u.w);
-        }
-        store4_sel<STREAM>(ubuf + orow + (size_t)c4 * 4, u);
-      }
-      v[it] = u;
-      ss += (u.x * u.x + u.y * u.y) + (u.z * u.z + u.w * u.w);
-    }
+    for (int j = 0; j < N; ++j) x[j] = load4_sel<STREAM>(in + (size_t)j * d + (size_t)c4 * 4);
+    u = premix4<N>(x, pre + (size_t)(l - 1) * N);
+    if (N > 1) store4_sel<STREAM>(ubuf + orow + (size_t)c4 * 4, u);
+    ss = sumsq4(u);
   }
   ss = block_sum(ss, sh);
-  const float r = 1.0f / sqrtf(ss / (float)d + eps);
-#pragma unroll
-  for (int it = 0; it < kMaxVec; ++it) {
-    const int c4 = threadIdx.x + it * (int)blockDim.x;
-    if (c4 < nv) {
-      float4 u = v[it];
-      u.x *= r; u.y *= r; u.z *= r; u.w *= r;
-      store4(xhat + orow + (size_t)c4 * 4, u);
-    }
+  const float r = inv_rms(ss, d, eps);
+  if (c4 < nv) {
+    u.x *= r; u.y *= r; u.z *= r; u.w *= r;
+    store4(xhat + orow + (size_t)c4 * 4, u);
   }
 }
 
@@ -490,6 +499,112 @@ __global__ __launch_bounds__(BT) void k_scan(float* trace, const float* __restri
   }
 }
 
+// The same correction with one workgroup per token row (thread c owns channels 4c .. 4c+3 of all N streams), which
+// also prepares the next round's evaluation: right after layer l's new state is known it forms the branch input of
+// layer l + 1 from it, u = sum_j pre_{l+1}[j] X_l[j], and its normalised form -- what k_premix_rmsnorm would
+// compute from the stored trace in a pass of its own, bit for bit (same premix4 / sumsq4 / block_sum / inv_rms, same
+// block shape).  Costs two workgroup barriers per layer; saves re-reading the new trace.  For batches large enough
+// that a row per workgroup fills the chip.  Ltot: number of layers of the model (no layer follows the last).
+template <int N, int U, bool PROBE, typename OutT, bool STREAM>
+__global__ __launch_bounds__(1024) void k_scan_norm(float* trace, const float* __restrict__ g,
+                                                         const float* __restrict__ Hres, const float* __restrict__ post,
+                                                         const float* __restrict__ pre, float* __restrict__ ubuf,
+                                                         OutT* __restrict__ xhat, int mode, int l0, int Lc, int Ltot, int M,
+                                                         int d, float eps, float* __restrict__ partials) {
+  extern __shared__ float sh[];   // [kMaxWaves] for the row sums, then [waves][2][Lc] when PROBE
+  float* shp = sh + kMaxWaves;
+  const int nv = d >> 2;
+  const int row = blockIdx.x, c4 = threadIdx.x;
+  const bool active = c4 < nv;
+  const size_t slot = (size_t)M * N * d;
+  const size_t toff = (size_t)row * N * d + (size_t)(active ? c4 : 0) * 4;
+  const size_t goff = (size_t)row * d + (size_t)(active ? c4 : 0) * 4;
+  const size_t gslot = (size_t)M * d;
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
+
+  float4 acc[N], prev_old[N];
+#pragma unroll
+  for (int j = 0; j < N; ++j) {
+    acc[j] = active ? *reinterpret_cast<const float4*>(trace + (size_t)(l0 - 1) * slot + toff + (size_t)j * d) : zero;
+    prev_old[j] = acc[j];
+  }
+  const int lend = l0 + Lc;
+  for (int lb = l0; lb < lend; lb += U) {
+    float4 gv[U];
+    float4 old[U][N];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int l = lb + u;
+      const bool ok = active && l < lend;
+      gv[u] = ok ? load4_sel<STREAM>(g + (size_t)(l - 1) * gslot + goff) : zero;
+      if (PROBE) {
+#pragma unroll
+        for (int j = 0; j < N; ++j) old[u][j] = ok ? load4_sel<STREAM>(trace + (size_t)l * slot + toff + (size_t)j * d) : zero;
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int l = lb + u;
+      if (l < lend) {   // uniform over the block
+        const float* Hl = Hres ? Hres + (size_t)(l - 1) * N * N : nullptr;
+        const float* pl = post ? post + (size_t)(l - 1) * N : nullptr;
+        float4 nw[N];
+        layer_step<N>(acc, gv[u], Hl, pl, mode, nw);
+        if (PROBE) {
+          float4 f[N];
+          layer_step<N>(prev_old, gv[u], Hl, pl, mode, f);
+          float rs = 0.f, ds = 0.f;
+#pragma unroll
+          for (int j = 0; j < N; ++j) {
+            rs += sqdiff4(old[u][j], f[j]);
+            ds += sqdiff4(nw[j], old[u][j]);
+          }
+          if (!active) { rs = 0.f; ds = 0.f; }
+          rs = wave_sum_lane63(rs);
+          ds = wave_sum_lane63(ds);
+          if (lane == kWave - 1) {
+            shp[(wave * 2 + 0) * Lc + (l - l0)] = rs;
+            shp[(wave * 2 + 1) * Lc + (l - l0)] = ds;
+          }
+#pragma unroll
+          for (int j = 0; j < N; ++j) prev_old[j] = old[u][j];
+        }
+        if (active) {
+#pragma unroll
+          for (int j = 0; j < N; ++j) *reinterpret_cast<float4*>(trace + (size_t)l * slot + toff + (size_t)j * d) = nw[j];
+        }
+        if (l < Ltot) {   // layer l + 1 reads this state next round: its input and normalised input (0-based index l)
+          float4 un = zero;
+          float ss = 0.f;
+          if (active) {
+            un = premix4<N>(nw, pre + (size_t)l * N);
+            if (N > 1) store4_sel<STREAM>(ubuf + (size_t)l * gslot + goff, un);
+            ss = sumsq4(un);
+          }
+          ss = block_sum(ss, sh);
+          const float r = inv_rms(ss, d, eps);
+          if (active) {
+            un.x *= r; un.y *= r; un.z *= r; un.w *= r;
+            store4(xhat + (size_t)l * gslot + goff, un);
+          }
+        }
+#pragma unroll
+        for (int j = 0; j < N; ++j) acc[j] = nw[j];
+      }
+    }
+  }
+  if (PROBE) {
+    __syncthreads();
+    const int nw_ = blockDim.x / kWave;
+    for (int i = threadIdx.x; i < 2 * Lc; i += blockDim.x) {
+      float sm = shp[i];
+      for (int w = 1; w < nw_; ++w) sm = sm + shp[w * 2 * Lc + i];
+      partials[(size_t)blockIdx.x * 2 * Lc + i] = sm;
+    }
+  }
+}
+
 // Diagonal surrogate A_l = diag(a_l) with caller-supplied a (Methods, "Diagonal Newton"; Alg. 3): for single-stream
 // traces,  h~ = h_{l-1}(old) + g_l;  h_l(new) = h~ + a_l * (h_{l-1}(new) - h_{l-1}(old)),  strict fp32, each
 // operation rounded once.  Same thread mapping, load grouping and probe as k_scan.
@@ -599,15 +714,31 @@ __global__ __launch_bounds__(kThreads) void k_transpose_bf16(const bf16_t* __res
 }  // namespace
 
 // ------------------------------------------------------------------------------------------------
-hipError_t launch_premix_rmsnorm(hipStream_t s, const Dims& D, int l0, int Lc, const float* trace,
-                                 const float* pre, float* ubuf, void* xhat, bool out_bf16) {
+namespace {
+template <int N>
+void launch_premix_n(hipStream_t s, const Dims& D, int l0, int Lc, const float* trace, const float* pre, float* ubuf,
+                     void* xhat, bool out_bf16) {
   dim3 grid(D.M, Lc), block(row_block_threads(D.d));
   const bool stream = (size_t)Lc * D.M * D.n * D.d * sizeof(float) > kStreamBytes;
   if (out_bf16) {
-    if (stream) hipLaunchKernelGGL((k_premix_rmsnorm<bf16_t, true>), grid, block, 0, s, trace, pre, ubuf, (bf16_t*)xhat, l0, D.M, D.n, D.d, D.eps);
-    else hipLaunchKernelGGL((k_premix_rmsnorm<bf16_t, false>), grid, block, 0, s, trace, pre, ubuf, (bf16_t*)xhat, l0, D.M, D.n, D.d, D.eps);
+    if (stream) hipLaunchKernelGGL((k_premix_rmsnorm<N, bf16_t, true>), grid, block, 0, s, trace, pre, ubuf, (bf16_t*)xhat, l0, D.M, D.d, D.eps);
+    else hipLaunchKernelGGL((k_premix_rmsnorm<N, bf16_t, false>), grid, block, 0, s, trace, pre, ubuf, (bf16_t*)xhat, l0, D.M, D.d, D.eps);
   } else
-    hipLaunchKernelGGL((k_premix_rmsnorm<float, false>), grid, block, 0, s, trace, pre, ubuf, (float*)xhat, l0, D.M, D.n, D.d, D.eps);
+    hipLaunchKernelGGL((k_premix_rmsnorm<N, float, false>), grid, block, 0, s, trace, pre, ubuf, (float*)xhat, l0, D.M, D.d, D.eps);
+}
+}  // namespace
+
+hipError_t launch_premix_rmsnorm(hipStream_t s, const Dims& D, int l0, int Lc, const float* trace,
+                                 const float* pre, float* ubuf, void* xhat, bool out_bf16) {
+  // pre == nullptr: the rows are taken as single-stream states whatever D.n says (chunk inputs of fused layers)
+  switch (pre ? D.n : 1) {
+    case 1: launch_premix_n<1>(s, D, l0, Lc, trace, pre, ubuf, xhat, out_bf16); break;
+    case 2: launch_premix_n<2>(s, D, l0, Lc, trace, pre, ubuf, xhat, out_bf16); break;
+    case 3: launch_premix_n<3>(s, D, l0, Lc, trace, pre, ubuf, xhat, out_bf16); break;
+    case 4: launch_premix_n<4>(s, D, l0, Lc, trace, pre, ubuf, xhat, out_bf16); break;
+    case 8: launch_premix_n<8>(s, D, l0, Lc, trace, pre, ubuf, xhat, out_bf16); break;
+    default: return hipErrorInvalidValue;
+  }
   return hipGetLastError();
 }
 
@@ -722,6 +853,46 @@ hipError_t launch_scan(hipStream_t s, const Dims& D, int mode, int l0, int Lc, f
   return hipGetLastError();
 }
 
+// ---- the correction that also prepares the next round's branch inputs (k_scan_norm)
+bool scan_fuses_norm(const Dims& D) { return (size_t)D.M * D.d > ((size_t)1 << 20) && D.d / 4 <= 1024; }
+int scan_norm_blocks(const Dims& D) { return D.M; }
+
+namespace {
+template <int N, int U>
+void launch_scan_norm_n(hipStream_t s, const Dims& D, int mode, int l0, int Lc, float* trace, const float* g,
+                        const float* Hres, const float* post, const float* pre, float* ubuf, void* xhat, bool out_bf16,
+                        float* partials) {
+  dim3 grid(D.M), block(row_block_threads(D.d));
+  const size_t shm = (kMaxWaves + (partials ? (size_t)(block.x / kWave) * 2 * Lc : 0)) * sizeof(float);
+  const bool stream = (size_t)Lc * D.M * D.n * D.d * sizeof(float) > kStreamBytes;
+#define SNLP_SCAN_NORM(PROBE_, OUT_, STREAM_)                                                                         \
+  hipLaunchKernelGGL((k_scan_norm<N, U, PROBE_, OUT_, STREAM_>), grid, block, shm, s, trace, g, Hres, post, pre, ubuf, \
+                     (OUT_*)xhat, mode, l0, Lc, D.L, D.M, D.d, D.eps, partials)
+  if (out_bf16) {
+    if (partials) { if (stream) SNLP_SCAN_NORM(true, bf16_t, true); else SNLP_SCAN_NORM(true, bf16_t, false); }
+    else { if (stream) SNLP_SCAN_NORM(false, bf16_t, true); else SNLP_SCAN_NORM(false, bf16_t, false); }
+  } else {
+    if (partials) SNLP_SCAN_NORM(true, float, false); else SNLP_SCAN_NORM(false, float, false);
+  }
+#undef SNLP_SCAN_NORM
+}
+}  // namespace
+
+hipError_t launch_scan_norm(hipStream_t s, const Dims& D, int mode, int l0, int Lc, float* trace, const float* g,
+                            const float* Hres, const float* post, const float* pre, float* ubuf, void* xhat,
+                            bool out_bf16, float* partials) {
+  if (!scan_fuses_norm(D)) return hipErrorInvalidValue;
+  switch (D.n) {
+    case 1: launch_scan_norm_n<1, 4>(s, D, mode, l0, Lc, trace, g, Hres, post, pre, ubuf, xhat, out_bf16, partials); break;
+    case 2: launch_scan_norm_n<2, 2>(s, D, mode, l0, Lc, trace, g, Hres, post, pre, ubuf, xhat, out_bf16, partials); break;
+    case 3: launch_scan_norm_n<3, 2>(s, D, mode, l0, Lc, trace, g, Hres, post, pre, ubuf, xhat, out_bf16, partials); break;
+    case 4: launch_scan_norm_n<4, 2>(s, D, mode, l0, Lc, trace, g, Hres, post, pre, ubuf, xhat, out_bf16, partials); break;
+    case 8: launch_scan_norm_n<8, 1>(s, D, mode, l0, Lc, trace, g, Hres, post, pre, ubuf, xhat, out_bf16, partials); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
 hipError_t launch_scan_diag(hipStream_t s, const Dims& D, int l0, int Lc, float* trace, const float* g,
                             const float* diag, float* partials) {
   if (D.n != 1) return hipErrorInvalidValue;
@@ -735,10 +906,10 @@ hipError_t launch_scan_diag(hipStream_t s, const Dims& D, int l0, int Lc, float*
 }
 
 hipError_t launch_probe_finalize(hipStream_t s, const Dims& D, int Lc, const float* partials, float* probe,
-                                 bool take_sqrt_first_only, int col0) {
+                                 bool take_sqrt_first_only, int col0, int nblk) {
   const int width = 2 * Lc;
   const int entries = take_sqrt_first_only ? Lc : width;
-  hipLaunchKernelGGL(k_probe_finalize, dim3(entries), dim3(kThreads), 0, s, partials, scan_partial_blocks(D), width,
+  hipLaunchKernelGGL(k_probe_finalize, dim3(entries), dim3(kThreads), 0, s, partials, nblk > 0 ? nblk : scan_partial_blocks(D), width,
                      probe, take_sqrt_first_only ? Lc : 0, col0, col0 + Lc);
   return hipGetLastError();
 }

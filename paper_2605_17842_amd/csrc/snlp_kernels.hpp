@@ -49,9 +49,19 @@ hipError_t launch_scan(hipStream_t s, const Dims& D, int mode, int l0, int Lc, f
 // Diagonal-surrogate correction (single-stream traces only), diag [L, M, d] fp32.
 hipError_t launch_scan_diag(hipStream_t s, const Dims& D, int l0, int Lc, float* trace, const float* g,
                             const float* diag, float* partials);
-// probe rows have col0 + Lc columns: the first col0 (sequential prefix) are written as zero.
+// The same correction (in place, dependent layers) that also leaves, for every layer l + 1 <= L after a layer l it
+// has corrected, the branch input of the next evaluation: ubuf[l] (n > 1) and xhat[l] = what launch_premix_rmsnorm would
+// compute from the new slot l, bit for bit.  Only for shapes with scan_fuses_norm(D); partials then have
+// scan_norm_blocks(D) rows.
+bool scan_fuses_norm(const Dims& D);
+int scan_norm_blocks(const Dims& D);
+hipError_t launch_scan_norm(hipStream_t s, const Dims& D, int mode, int l0, int Lc, float* trace, const float* g,
+                            const float* Hres, const float* post, const float* pre, float* ubuf, void* xhat,
+                            bool out_bf16, float* partials);
+// probe rows have col0 + Lc columns: the first col0 (sequential prefix) are written as zero.  nblk: rows of `partials`
+// (<= 0: scan_partial_blocks(D)).
 hipError_t launch_probe_finalize(hipStream_t s, const Dims& D, int Lc, const float* partials, float* probe,
-                                 bool take_sqrt_first_only, int col0 = 0);
+                                 bool take_sqrt_first_only, int col0 = 0, int nblk = -1);
 // bf16 [L][K][N] -> [L][N][K] (one-time weight repack).
 hipError_t launch_transpose_bf16(hipStream_t s, const bf16_t* in, bf16_t* out, int L, int K, int N);
 

@@ -83,16 +83,18 @@ def check_iterates(gh, shp, t, mode, Ks, tol, check_seq=True, check_probe=True):
 # Small batches (M d <= 2^20): one wave per block, operands through the caches -- k_scan<N, U, ., ., 64, false>.
 SCAN_SMALL = [(1, oc.IDN, 5, 37, 132), (4, oc.HCN, 6, 19, 260), (4, oc.IDN, 3, 8, 64), (2, oc.HCN, 9, 300, 128),
               (3, oc.HCN, 4, 5, 16), (8, oc.HCN, 3, 7, 32), (1, oc.IDN, 26, 64, 1664)]
-# The sizes the prefill workloads run (M d > 2^20: 256-thread blocks with the 4-wave probe reduction; a launch whose
-# trace exceeds 128 MB streams its operands with non-temporal loads).  Template reached, from scan_block_threads and
-# kStreamBytes in the launcher:
+# The sizes the prefill workloads run (M d > 2^20).  There snlp_correction_scan, like a round of snlp_iterate, runs the
+# row-per-workgroup kernel that also prepares the next round's normalised inputs (k_scan_norm<N, U, PROBE, OutT, STREAM>;
+# a launch whose trace exceeds 128 MB streams its operands with non-temporal loads); the 256-thread k_scan variants
+# remain for the read-only probe, the one-shot-forward initialisation and the allocation-free entry point
+# (test_zz_no_alloc.py, test_prefill_size_scan_variants_agree below).
 SCAN_PREFILL = [
-    (4, oc.HCN, 20, 2048, 1280),   # d20 HCN workload: 839 MB of trace -> k_scan<4, 2, ., ., 256, true>
-    (1, oc.IDN, 26, 4096, 1664),   # d26 long prefill: 709 MB            -> k_scan<1, 4, ., ., 256, true>
-    (1, oc.IDN, 12, 2048, 768),    # d12 prefill: 75 MB                   -> k_scan<1, 4, ., ., 256, false>
-    (4, oc.HCN, 5, 1024, 1280),    # 105 MB                               -> k_scan<4, 2, ., ., 256, false>
-    (4, oc.IDN, 3, 1024, 1280),    # H = I block on four streams          -> k_scan<4, 2, ., ., 256, false>, mode IDN
-    (2, oc.HCN, 7, 2048, 1280),    # 147 MB                               -> k_scan<2, 2, ., ., 256, true>
+    (4, oc.HCN, 20, 2048, 1280),   # d20 HCN workload: 839 MB of trace -> k_scan_norm<4, 2, ., float, false> (fp32 context: never streamed)
+    (1, oc.IDN, 26, 4096, 1664),   # d26 long prefill: 709 MB            -> k_scan_norm<1, 4, ...>
+    (1, oc.IDN, 12, 2048, 768),    # d12 prefill: 75 MB
+    (4, oc.HCN, 5, 1024, 1280),
+    (4, oc.IDN, 3, 1024, 1280),    # H = I block on four streams, mode IDN
+    (2, oc.HCN, 7, 2048, 1280),
 ]
 
 
@@ -132,6 +134,79 @@ def test_correction_scan_bit_exact_and_probe(gh, n, mode, L, M, d):
     m.correction_scan(mode, torch.from_numpy(g).to(tr.device), None)
     torch.cuda.synchronize()
     assert np.array_equal(tr.cpu().numpy().view(np.uint32), ref.view(np.uint32))
+    m.close()
+
+
+@pytest.mark.parametrize("n,mode,L,M,d", [(4, oc.HCN, 20, 2048, 1280), (1, oc.IDN, 26, 4096, 1664), (1, oc.IDN, 12, 2048, 768),
+                                          (4, oc.IDN, 3, 1024, 1280)])
+def test_prefill_size_scan_variants_agree(gh, n, mode, L, M, d):
+    """The 256-thread k_scan variants at prefill sizes (streamed above 128 MB of trace: k_scan<N, U, ., ., 256, true / false>),
+    reached through the allocation-free entry point, against the oracle bit for bit, probe included."""
+    import paper_2605_17842_amd as snlp
+    say("static scan n=%d mode=%d L=%d M=%d d=%d" % (n, mode, L, M, d))
+    rng = np.random.default_rng(400 + n + L)
+    Hres = rng.uniform(0, 1, (L, n, n)).astype(np.float32)
+    post = rng.uniform(0.5, 2, (L, n)).astype(np.float32)
+    md = oc.Model(L=L, d=d, n_heads=1, head_dim=d, d_mlp=1, B=1, T=M, P=0, Wqkv=[], Wo=[], Wfc=[], Wproj=[],
+                  n_streams=n, Hres=Hres, pre=np.ones((L, n), np.float32), post=post)
+    old = rng.standard_normal((L + 1, M, n, d)).astype(np.float32)
+    g = rng.standard_normal((L, M, d)).astype(np.float32)
+    dev = torch.device("cuda:0")
+    tr = torch.from_numpy(old).to(dev)
+    probe = torch.zeros((2, L), dtype=torch.float32, device=dev)
+    snlp.correction_scan_static(mode, tr, torch.from_numpy(g).to(dev), torch.from_numpy(Hres).to(dev) if n > 1 else None,
+                                torch.from_numpy(post).to(dev) if n > 1 else None, probe)
+    torch.cuda.synchronize()
+    ref = oc.correction_scan(md, old[0], g, mode)
+    assert np.array_equal(tr.cpu().numpy().view(np.uint32), ref.view(np.uint32))
+    gp = probe.cpu().numpy().astype(np.float64)
+    assert np.allclose(gp[0], oc.residual_sq(md, old, g, mode), rtol=1e-5, atol=0)
+    assert np.allclose(gp[1], np.sum((ref[1:].astype(np.float64) - old[1:].astype(np.float64)) ** 2, axis=(1, 2, 3)), rtol=1e-5, atol=0)
+
+
+@pytest.mark.parametrize("n,bf16", [(1, True), (4, True), (2, False)])
+def test_correction_leaves_next_rounds_normalised_inputs(gh, n, bf16):
+    """Large batches: the correction kernel also writes the (pre-mixed and) normalised branch inputs of the next round.
+    They must be the bits the stand-alone norm pass computes from the new trace, the rounds that use them must equal
+    rounds that do not, and K = L must still be the sequential trace bit for bit."""
+    import paper_2605_17842_amd as snlp
+    shp = si.Shape("next_inputs", L=3, d=1280, n_heads=10, head_dim=128, d_mlp=1280, B=2, T=448, P=0, n_streams=n, bf16=bf16,
+                   seed=210 + n)      # M d = 1.15M > 2^20: one token row per workgroup in the correction
+    t = si.generate(shp)
+    if n > 1:                         # distinct streams, so that the pre-mix matters
+        t["h0"] = (t["h0"] + np.random.default_rng(3).standard_normal(t["h0"].shape).astype(np.float32)).astype(np.float32)
+    mode = oc.HCN if n > 1 else oc.IDN
+    m = gh.gpu_model(shp, t)
+    m.h0 = torch.from_numpy(t["h0"]).to(m.device)
+    m.init_trace(m.h0)
+    m.iterate(mode, 1, None)
+    torch.cuda.synchronize()
+    left_x, left_u = m.stage_buffer("xhat"), (m.stage_buffer("u") if n > 1 else None)
+    after1 = m.trace.clone()
+    m.bind_trace(m.trace)                              # forget the cached inputs: the next evaluation recomputes them
+    m.evaluate_branches()
+    torch.cuda.synchronize()
+    fresh_x, fresh_u = m.stage_buffer("xhat"), (m.stage_buffer("u") if n > 1 else None)
+    per = shp.M * shp.d
+    assert torch.equal(left_x.view(torch.int16 if bf16 else torch.int32)[per:], fresh_x.view(torch.int16 if bf16 else torch.int32)[per:])
+    if n > 1:
+        assert torch.equal(left_u.view(torch.int32)[per:], fresh_u.view(torch.int32)[per:])
+    # two more rounds with and without the cached inputs
+    m.iterate(mode, 2, None)
+    a = m.trace.clone()
+    m.trace.copy_(after1)
+    m.bind_trace(m.trace)
+    m.iterate(mode, 1, None)
+    m.bind_trace(m.trace)
+    m.iterate(mode, 1, None)
+    torch.cuda.synchronize()
+    assert torch.equal(a, m.trace)
+    assert torch.equal(a, m.sequential_forward(mode, m.h0))          # L = 3 rounds in all
+    md = oracle_model(shp, t, widen=True)
+    ref, _, _ = oc.iterate(md, oc.init_trace(md, t["h0"]), mode, 2)
+    m.init_trace(m.h0)
+    m.iterate(mode, 2, None)
+    assert per_layer_rel_err(np_trace(m), ref).max() < (TOL_BF16 if bf16 else TOL_F32)
     m.close()
 
 
@@ -495,6 +570,7 @@ def test_leaving_converged_layers_out(gh, n, S, init):
     b = m.trace.clone()
     m.set_skip_converged(False)
     m.trace.copy_(edited)
+    m.bind_trace(m.trace)                                # the caller wrote into the bound trace: bind it again
     m.iterate(mode, 1, None)
     torch.cuda.synchronize()
     assert torch.equal(b, m.trace)
