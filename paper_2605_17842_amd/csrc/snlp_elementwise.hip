@@ -854,6 +854,7 @@ hipError_t launch_scan(hipStream_t s, const Dims& D, int mode, int l0, int Lc, f
 }
 
 // ---- the correction that also prepares the next round's branch inputs (k_scan_norm)
+// Decode-sized batches keep the two kernels: with 128 rows the row-per-workgroup form measured 31 us against 18.5 + 7.7.
 bool scan_fuses_norm(const Dims& D) { return (size_t)D.M * D.d > ((size_t)1 << 20) && D.d / 4 <= 1024; }
 int scan_norm_blocks(const Dims& D) { return D.M; }
 

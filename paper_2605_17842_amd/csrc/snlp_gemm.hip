@@ -475,36 +475,22 @@ hipError_t launch_ring(hipStream_t s, int Lc, int M, int N, int K, const bf16_t*
 // serves TN MFMAs and the layer's A is re-read from L2 by N / BN workgroups instead of N / 128; k runs in
 // order for every TN, so results depend neither on the layer count nor on the tile width.  Measured: time is
 // close to (weight bytes + re-read A bytes) / 6-7 TB/s.
+// One wave's share of a skinny-GEMM workgroup: TN column blocks from block nb0 on, all BM rows.  The waves of a
+// workgroup may run this with different TN (the staging of the token tile and the barriers do not depend on it).
 template <int TM, int TN, int NW, int DEPTH, int EPI, bool C_BF16>
-__global__ __launch_bounds__(64 * NW, TN == 1 ? 2 : 1) void k_gemm_skinny(const bf16_t* __restrict__ A, size_t sA,
-                                                                     const bf16_t* __restrict__ Wp, size_t sW, void* Cv,
-                                                                     size_t sC, const float* __restrict__ R, size_t sR,
-                                                                     int M, int N, int K, int tiles_m, int tiles_n,
-                                                                     unsigned total_tiles, int a_group) {
+__device__ __forceinline__ void skinny_wave(const bf16_t* __restrict__ A, const bf16_t* __restrict__ Wp, void* Cv, size_t sC,
+                                            const float* __restrict__ R, size_t sR, int M, int N, int K, int layer, int m0,
+                                            int nb0, bf16_t* lds) {
   constexpr int BM = 32 * TM;
   constexpr int NT = 64 * NW;
   constexpr int TILE = BM * kLdsRow;                 // one staged A tile, elements
   constexpr int PA = (BM * 8 + NT - 1) / NT;         // 16-byte A chunks per thread per k-tile
   static_assert(DEPTH == 8 || DEPTH == 16, "weight queue holds 2 or 4 whole k-tiles");
-  __shared__ __attribute__((aligned(16))) bf16_t lds[4 * TILE];   // ring of four A tiles
-
-  // XCD-aware order: consecutive logical tiles (same layer and row tile, neighbouring columns: same A) on one XCD
-  const unsigned q = total_tiles / 8, rr = total_tiles % 8;
-  const unsigned xcd = blockIdx.x % 8, local = blockIdx.x / 8;
-  const unsigned t = xcd * q + (xcd < rr ? xcd : rr) + local;
-  const unsigned per_layer = (unsigned)tiles_m * (unsigned)tiles_n;
-  const int layer = (int)(t / per_layer);
-  const int tm = (int)((t % per_layer) / (unsigned)tiles_n), tn = (int)(t % (unsigned)tiles_n);
-  const int m0 = tm * BM;   // first row of this workgroup's row tile
-  A += (size_t)(layer / a_group) * sA;
-  Wp += (size_t)layer * sW;
-
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int nk = K / kBK, nsteps = nk * 4;
 
   // weight streams of this wave: TN column blocks nb0 .. nb0+TN-1 (clamped: a block past the last one streams the
   // last one and stores nothing), 512 elements (1 KB) per k-step each
-  const int nb0 = (tn * NW + wave) * TN;
   const int nblocks = N / 32;
   const bf16x8_t* wsrc[TN];
 #pragma unroll
@@ -654,6 +640,38 @@ __global__ __launch_bounds__(64 * NW, TN == 1 ? 2 : 1) void k_gemm_skinny(const 
   }
 }
 
+// TN_HI column blocks for the first NH waves, TN_LO for the others (NH = NW: all alike): a workgroup owns
+// NH TN_HI + (NW - NH) TN_LO consecutive column blocks, which lets the column tile follow N * layers / compute units
+// more closely than a multiple of NW blocks would.
+template <int TM, int TN_HI, int TN_LO, int NH, int NW, int DEPTH, int EPI, bool C_BF16>
+__global__ __launch_bounds__(64 * NW, TN_HI == 1 ? 2 : 1) void k_gemm_skinny(const bf16_t* __restrict__ A, size_t sA,
+                                                                        const bf16_t* __restrict__ Wp, size_t sW, void* Cv,
+                                                                        size_t sC, const float* __restrict__ R, size_t sR,
+                                                                        int M, int N, int K, int tiles_m, int tiles_n,
+                                                                        unsigned total_tiles, int a_group) {
+  constexpr int BM = 32 * TM;
+  constexpr int TILE = BM * kLdsRow;
+  constexpr int BLOCKS = NH * TN_HI + (NW - NH) * TN_LO;   // column blocks per workgroup
+  __shared__ __attribute__((aligned(16))) bf16_t lds[4 * TILE];   // ring of four A tiles
+
+  // XCD-aware order: consecutive logical tiles (same layer and row tile, neighbouring columns: same A) on one XCD
+  const unsigned q = total_tiles / 8, rr = total_tiles % 8;
+  const unsigned xcd = blockIdx.x % 8, local = blockIdx.x / 8;
+  const unsigned t = xcd * q + (xcd < rr ? xcd : rr) + local;
+  const unsigned per_layer = (unsigned)tiles_m * (unsigned)tiles_n;
+  const int layer = (int)(t / per_layer);
+  const int tm = (int)((t % per_layer) / (unsigned)tiles_n), tn = (int)(t % (unsigned)tiles_n);
+  const int m0 = tm * BM;   // first row of this workgroup's row tile
+  A += (size_t)(layer / a_group) * sA;
+  Wp += (size_t)layer * sW;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  if (NH == NW || wave < NH)
+    skinny_wave<TM, TN_HI, NW, DEPTH, EPI, C_BF16>(A, Wp, Cv, sC, R, sR, M, N, K, layer, m0, tn * BLOCKS + wave * TN_HI, lds);
+  else
+    skinny_wave<TM, TN_LO, NW, DEPTH, EPI, C_BF16>(A, Wp, Cv, sC, R, sR, M, N, K, layer, m0,
+                                                   tn * BLOCKS + NH * TN_HI + (wave - NH) * TN_LO, lds);
+}
+
 // [L][K][N] row-major -> operand order [L][N/32][K/16][64][8]
 __global__ __launch_bounds__(kThreads) void k_repack_operand_order(const bf16_t* __restrict__ in, bf16_t* __restrict__ out,
                                                                     int K, int N) {
@@ -670,15 +688,16 @@ __global__ __launch_bounds__(kThreads) void k_repack_operand_order(const bf16_t*
   for (int e = 0; e < 8; ++e) dst[e] = v[e];
 }
 
-template <int TM, int TN, int NW, int DEPTH>
+template <int TM, int TN, int NW, int DEPTH, int TN_LO = TN, int NH = NW>
 hipError_t launch_skinny(hipStream_t s, int Lc, int M, int N, int K, const bf16_t* A, size_t sA, const bf16_t* Wp,
                          size_t sW, void* C, size_t sC, bool c_bf16, int epi, const float* R, size_t sR, int a_group) {
-  const int tiles_n = (N + 32 * NW * TN - 1) / (32 * NW * TN), tiles_m = (M + 32 * TM - 1) / (32 * TM);
+  constexpr int BLOCKS = NH * TN + (NW - NH) * TN_LO;   // 32-column blocks per workgroup
+  const int tiles_n = (N + 32 * BLOCKS - 1) / (32 * BLOCKS), tiles_m = (M + 32 * TM - 1) / (32 * TM);
   const unsigned total = (unsigned)Lc * tiles_m * tiles_n;
   dim3 grid(total), block(64 * NW);
 #define SNLP_SKINNY_LAUNCH(EPI_, CB_)                                                                           \
-  hipLaunchKernelGGL((k_gemm_skinny<TM, TN, NW, DEPTH, EPI_, CB_>), grid, block, 0, s, A, sA, Wp, sW, C, sC, R, sR, M, N, K, \
-                     tiles_m, tiles_n, total, a_group)
+  hipLaunchKernelGGL((k_gemm_skinny<TM, TN, TN_LO, NH, NW, DEPTH, EPI_, CB_>), grid, block, 0, s, A, sA, Wp, sW, C, sC, R, sR, \
+                     M, N, K, tiles_m, tiles_n, total, a_group)
   if (epi == EPI_STORE && c_bf16) SNLP_SKINNY_LAUNCH(EPI_STORE, true);
   else if (epi == EPI_STORE) SNLP_SKINNY_LAUNCH(EPI_STORE, false);
   else if (epi == EPI_RELU2 && c_bf16) SNLP_SKINNY_LAUNCH(EPI_RELU2, true);
@@ -714,6 +733,20 @@ hipError_t launch_skinny_tm(hipStream_t s, int Lc, int M, int N, int K, const bf
         return launch_skinny<1, 1, 2, 16>(s, Lc, M, N, K, A, sA, Wp, sW, C, sC, c_bf16, epi, R, sR, a_group);
       return launch_skinny<1, 1, 1, 16>(s, Lc, M, N, K, A, sA, Wp, sW, C, sC, c_bf16, epi, R, sR, a_group);
     }
+  }
+  // Column tiles that follow the launch: with wpl = 256 / layers workgroups per layer the 256 compute units take one
+  // workgroup each, so a workgroup should own ceil(blocks / wpl) column blocks.  Where that is 9 or 10 blocks (d20
+  // QKV: 120 blocks, 12 workgroups per layer instead of 10 of 12 blocks) or 13 or 14 (d20 FC: 160 blocks, 12 workgroups
+  // instead of 10 of 16), the waves of a workgroup take unequal shares: 3 3 2 2, or 2 2 2 2 2 2 1 1 with eight waves.
+  // Fewer weight bytes per compute unit at the same token-tile bytes, and 240 compute units busy instead of 200.
+  if (TM >= 2 && Lc <= 256) {
+    const int nblocks = N / 32, wpl = 256 / Lc;
+    const int want = (nblocks + wpl - 1) / wpl;
+    const long wgs10 = (long)Lc * ((nblocks + 9) / 10), wgs14 = (long)Lc * ((nblocks + 13) / 14);
+    if ((want == 9 || want == 10) && wgs10 >= 180 && wgs10 <= 256)
+      return launch_skinny<TM, 3, 4, 8, 2, 2>(s, Lc, M, N, K, A, sA, Wp, sW, C, sC, c_bf16, epi, R, sR, a_group);
+    if ((want == 13 || want == 14) && wgs14 >= 180 && wgs14 <= 256)
+      return launch_skinny<TM, 2, 8, 8, 1, 6>(s, Lc, M, N, K, A, sA, Wp, sW, C, sC, c_bf16, epi, R, sR, a_group);
   }
   int tn_pick = 1;
   for (int tn = 4; tn >= 2; --tn) {
