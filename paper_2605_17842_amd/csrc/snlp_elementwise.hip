@@ -94,6 +94,20 @@ __device__ __forceinline__ float block_sum(float v, float* sh /*[kMaxWaves]*/) {
   return t;
 }
 
+// The same sum (same order, same bits) with one barrier: for callers that alternate between two scratch arrays, so that a
+// thread still reading the previous total cannot meet the next call's writes (the barrier of the call in between
+// separates them).
+__device__ __forceinline__ float block_sum_alternating(float v, float* sh /*[kMaxWaves], other array than last call*/) {
+  v = wave_sum(v);
+  const int w = threadIdx.x / kWave;
+  const int nw = blockDim.x / kWave;
+  if ((threadIdx.x & (kWave - 1)) == 0) sh[w] = v;
+  __syncthreads();
+  float t = sh[0];
+  for (int i = 1; i < nw; ++i) t = t + sh[i];
+  return t;
+}
+
 // Threads per block of the row kernels: one float4 per thread when the row allows it (rows of d / 4 float4).
 static inline int row_block_threads(int d) {
   const int nv = d / 4;
@@ -503,7 +517,7 @@ __global__ __launch_bounds__(BT) void k_scan(float* trace, const float* __restri
 // also prepares the next round's evaluation: right after layer l's new state is known it forms the branch input of
 // layer l + 1 from it, u = sum_j pre_{l+1}[j] X_l[j], and its normalised form -- what k_premix_rmsnorm would
 // compute from the stored trace in a pass of its own, bit for bit (same premix4 / sumsq4 / block_sum / inv_rms, same
-// block shape).  Costs two workgroup barriers per layer; saves re-reading the new trace.  For batches large enough
+// block shape).  Costs one workgroup barrier per layer; saves re-reading the new trace.  For batches large enough
 // that a row per workgroup fills the chip.  Ltot: number of layers of the model (no layer follows the last).
 template <int N, int U, bool PROBE, typename OutT, bool STREAM>
 __global__ __launch_bounds__(1024) void k_scan_norm(float* trace, const float* __restrict__ g,
@@ -511,8 +525,8 @@ __global__ __launch_bounds__(1024) void k_scan_norm(float* trace, const float* _
                                                          const float* __restrict__ pre, float* __restrict__ ubuf,
                                                          OutT* __restrict__ xhat, int mode, int l0, int Lc, int Ltot, int M,
                                                          int d, float eps, float* __restrict__ partials) {
-  extern __shared__ float sh[];   // [kMaxWaves] for the row sums, then [waves][2][Lc] when PROBE
-  float* shp = sh + kMaxWaves;
+  extern __shared__ float sh[];   // [2][kMaxWaves] for the row sums (alternating by layer), then [waves][2][Lc] when PROBE
+  float* shp = sh + 2 * kMaxWaves;
   const int nv = d >> 2;
   const int row = blockIdx.x, c4 = threadIdx.x;
   const bool active = c4 < nv;
@@ -582,7 +596,7 @@ __global__ __launch_bounds__(1024) void k_scan_norm(float* trace, const float* _
             if (N > 1) store4_sel<STREAM>(ubuf + (size_t)l * gslot + goff, un);
             ss = sumsq4(un);
           }
-          ss = block_sum(ss, sh);
+          ss = block_sum_alternating(ss, sh + (l & 1) * kMaxWaves);
           const float r = inv_rms(ss, d, eps);
           if (active) {
             un.x *= r; un.y *= r; un.z *= r; un.w *= r;
@@ -864,7 +878,7 @@ void launch_scan_norm_n(hipStream_t s, const Dims& D, int mode, int l0, int Lc, 
                         const float* Hres, const float* post, const float* pre, float* ubuf, void* xhat, bool out_bf16,
                         float* partials) {
   dim3 grid(D.M), block(row_block_threads(D.d));
-  const size_t shm = (kMaxWaves + (partials ? (size_t)(block.x / kWave) * 2 * Lc : 0)) * sizeof(float);
+  const size_t shm = (2 * kMaxWaves + (partials ? (size_t)(block.x / kWave) * 2 * Lc : 0)) * sizeof(float);
   const bool stream = (size_t)Lc * D.M * D.n * D.d * sizeof(float) > kStreamBytes;
 #define SNLP_SCAN_NORM(PROBE_, OUT_, STREAM_)                                                                         \
   hipLaunchKernelGGL((k_scan_norm<N, U, PROBE_, OUT_, STREAM_>), grid, block, shm, s, trace, g, Hres, post, pre, ubuf, \
