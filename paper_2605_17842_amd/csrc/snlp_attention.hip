@@ -363,7 +363,7 @@ __device__ __forceinline__ void rope_qknorm_frags(bf16x8_t (&f)[4], const float*
 }
 
 
-__global__ __launch_bounds__(kThreads) void k_attn_bf16_decode(const bf16_t* __restrict__ qkv,
+__global__ __launch_bounds__(kThreads, 2) void k_attn_bf16_decode(const bf16_t* __restrict__ qkv,
                                                                 const bf16_t* __restrict__ Kpre,
                                                                 const bf16_t* __restrict__ Vpre,
                                                                 bf16_t* __restrict__ out, int l0, int M, int T, int P,
