@@ -1,11 +1,16 @@
 // Layer-batched grouped GEMMs of the SNLP evaluation step (Eq. (4); "batched form" of Methods,
 // "Layer fusion": per-layer weights stacked, all layers evaluated in one grouped operation).
 //   C[l] = epilogue(A[l] (M x K) * W[l] (K x N)),  l = 0..Lc-1, one launch for all layers.
-// bf16 path: MFMA v_mfma_f32_32x32x16_bf16 with fp32 accumulation, operands K-contiguous
-// (A [M, K], weights repacked to [N, K]), tiles staged through padded LDS, next tile prefetched
-// into registers while the current one is multiplied.  The work of one output tile never depends on
-// the number of layers in the launch, so a layer computes bit-identical results whether it is
-// launched alone (sequential execution, Alg. 1) or in the batch (Alg. 2).
+// bf16 path: MFMA v_mfma_f32_32x32x16_bf16 with fp32 accumulation.  Three kernels:
+//   k_gemm_bf16_256  M > 128, launches with many tiles: 256 x 256 (or 256 x 128) x 64 tiles, both operands through a
+//                    five-unit LDS ring filled by direct-to-LDS loads; weights repacked [N, K];
+//   k_gemm_bf16      M > 128, small launches: 128 x 128 tiles staged through padded LDS from registers;
+//   k_gemm_skinny    M <= 128: weights streamed from HBM straight into operand registers (repacked into MFMA operand
+//                    order), only the token tile through LDS.
+// Which kernel and which tile shape a launch gets depends on its size, the number of layers in it included.  What
+// never depends on it is the arithmetic of an output element: every kernel and every tile shape accumulates the
+// same k-ordered sequence of 32 x 32 x 16 MFMAs and applies the same epilogue, so a layer computes bit-identical
+// results whether it is launched alone (sequential execution, Alg. 1) or in the batch (Alg. 2).
 #include "snlp_kernels.hpp"
 
 namespace snlp {
@@ -808,8 +813,9 @@ hipError_t launch_repack_weights(hipStream_t s, const bf16_t* in, bf16_t* out, i
   return launch_transpose_bf16(s, in, out, L, K, N);
 }
 
-// Kernel and tile shape are functions of (M, N, K) only -- never of the layer count -- so that a layer's
-// result does not depend on how many layers share the launch.
+// The choice of kernel and tile shape follows the launch size (layers included); an output element's k-ordered MFMA
+// sequence and epilogue are the same in all of them, so a layer's result does not depend on how many layers share the
+// launch (tested bit for bit: K = L rounds against the one-layer launches of the sequential forward).
 hipError_t launch_gemm_bf16(hipStream_t s, int Lc, int M, int N, int K, const bf16_t* A, size_t sA, const bf16_t* W,
                             size_t sW, void* C, size_t sC, bool c_bf16, int epi, const float* R, size_t sR, int a_group) {
   if (!gemm_bf16_supported(M, N, K)) return hipErrorInvalidValue;
