@@ -79,10 +79,27 @@ class Model:
     post: Optional[np.ndarray] = None     # [L, n] fp32  (H^post, a column vector: 1 -> n streams)
     rope_base: float = 1.0e4
     rms_eps: float = 1.0e-6
+    # Test aid, off by default (the definition above is then evaluated in fp64 throughout): round to bfloat16 at the
+    # points where a bf16-operand implementation stores an operand -- the normalised inputs, q / k / v, the rotated
+    # and normalised q and k, the softmax probabilities that multiply v, the heads' outputs, the hidden activations.
+    # It changes no formula; it lets a comparison with such an implementation use a tolerance set by accumulation
+    # order instead of by operand rounding.
+    round_bf16: bool = False
 
     @property
     def M(self) -> int:
         return self.B * self.T
+
+
+def bf16_round(x: np.ndarray) -> np.ndarray:
+    """Nearest-even rounding to bfloat16 (via fp32), returned as fp64."""
+    u = np.ascontiguousarray(x, dtype=f32).view(np.uint32)
+    r = ((u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) >> np.uint32(16)) << np.uint32(16)
+    return r.astype(np.uint32).view(f32).astype(f64)
+
+
+def _operand(model: "Model", x: np.ndarray) -> np.ndarray:
+    return bf16_round(x) if model.round_bf16 else x
 
 
 # ----------------------------------------------------------------------------
@@ -111,7 +128,7 @@ def apply_rope(x: np.ndarray, cos: np.ndarray, sin: np.ndarray) -> np.ndarray:
 
 
 def attention(q: np.ndarray, k: np.ndarray, v: np.ndarray,
-              kpre: Optional[np.ndarray], vpre: Optional[np.ndarray]) -> np.ndarray:
+              kpre: Optional[np.ndarray], vpre: Optional[np.ndarray], round_p=None) -> np.ndarray:
     """Softmax attention of one layer; q, k, v are [B, H, T, dh], prefix [B, H, P, dh].
 
     Query t sees every prefix row and block rows t' <= t; scores are
@@ -134,8 +151,11 @@ def attention(q: np.ndarray, k: np.ndarray, v: np.ndarray,
             s = np.where(visible, s, -np.inf)
             s = s - s.max(axis=-1, keepdims=True)
             e = np.exp(s)
-            p = e / e.sum(axis=-1, keepdims=True)
-            out[b, h] = p @ vals
+            if round_p is None:
+                p = e / e.sum(axis=-1, keepdims=True)
+                out[b, h] = p @ vals
+            else:       # test aid: the probabilities multiply v as rounded operands, their sum stays unrounded
+                out[b, h] = (round_p(e) @ vals) / e.sum(axis=-1, keepdims=True)
     return out
 
 
@@ -145,13 +165,13 @@ def qkv_heads(model: Model, l: int, u: np.ndarray) -> Tuple[np.ndarray, np.ndarr
     md = model
     B, T, H, dh = md.B, md.T, md.n_heads, md.head_dim
     u = np.asarray(u, dtype=f64)
-    x = rmsnorm(u, md.rms_eps)
-    qkv = x @ np.asarray(md.Wqkv[l - 1], dtype=f64)                        # [M, 3d]
+    x = _operand(md, rmsnorm(u, md.rms_eps))
+    qkv = _operand(md, x @ np.asarray(md.Wqkv[l - 1], dtype=f64))          # [M, 3d]
     qkv = qkv.reshape(B, T, 3, H, dh).transpose(2, 0, 3, 1, 4)             # [3, B, H, T, dh]
     q, k, v = qkv[0], qkv[1], qkv[2]
     cos, sin = rope_cos_sin(md.P + np.arange(T), dh, md.rope_base)
-    q = rmsnorm(apply_rope(q, cos, sin), md.rms_eps)
-    k = rmsnorm(apply_rope(k, cos, sin), md.rms_eps)
+    q = _operand(md, rmsnorm(apply_rope(q, cos, sin), md.rms_eps))
+    k = _operand(md, rmsnorm(apply_rope(k, cos, sin), md.rms_eps))
     return q, k, np.ascontiguousarray(v)
 
 
@@ -161,7 +181,10 @@ def attn_heads(model: Model, l: int, u: np.ndarray) -> np.ndarray:
     q, k, v = qkv_heads(md, l, u)
     kpre = md.Kpre[l - 1] if md.Kpre is not None else None
     vpre = md.Vpre[l - 1] if md.Vpre is not None else None
-    o = attention(q, k, v, kpre, vpre)                                     # [B, H, T, dh]
+    if md.round_bf16:
+        o = _operand(md, attention(q, k, v, kpre, vpre, round_p=bf16_round))
+    else:
+        o = attention(q, k, v, kpre, vpre)                                 # [B, H, T, dh]
     return o.transpose(0, 2, 1, 3).reshape(md.B * md.T, md.d)
 
 
@@ -172,8 +195,8 @@ def attn_update(model: Model, l: int, u: np.ndarray) -> np.ndarray:
 
 def mlp_update(model: Model, l: int, u_mid: np.ndarray) -> np.ndarray:
     """m_l(u') = relu(norm(u') Wfc_l)^2 Wproj_l at the post-attention state u' [M, d]; fp64."""
-    x2 = rmsnorm(np.asarray(u_mid, dtype=f64), model.rms_eps)
-    hid = np.maximum(x2 @ np.asarray(model.Wfc[l - 1], dtype=f64), 0.0) ** 2
+    x2 = _operand(model, rmsnorm(np.asarray(u_mid, dtype=f64), model.rms_eps))
+    hid = _operand(model, np.maximum(x2 @ np.asarray(model.Wfc[l - 1], dtype=f64), 0.0) ** 2)
     return hid @ np.asarray(model.Wproj[l - 1], dtype=f64)
 
 

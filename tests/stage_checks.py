@@ -118,22 +118,40 @@ def oracle_stages(md: oc.Model, l: int, X_prev: np.ndarray) -> Dict[str, np.ndar
     return {"u": u, "q": rows(q), "k": rows(k), "v": rows(v), "attn": attn, "a": a, "m": m}
 
 
-def compare_stages(got: Dict[str, np.ndarray], ref: Dict[str, np.ndarray], n_streams: int, rotated_qk: bool) -> Dict[str, float]:
-    """Row-wise relative errors of the stage outputs present in `got` (same keys as oracle_stages)."""
+def fro_rel_err(x: np.ndarray, ref: np.ndarray) -> float:
+    """|| x - ref ||_F / || ref ||_F over the whole stage output, fp64."""
+    x = np.asarray(x, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    return float(np.linalg.norm(x - ref) / max(np.linalg.norm(ref), 1e-300))
+
+
+def compare_stages(got: Dict[str, np.ndarray], ref: Dict[str, np.ndarray], n_streams: int, rotated_qk: bool,
+                   metric: Callable = None) -> Dict[str, float]:
+    """Relative errors of the stage outputs present in `got` (same keys as oracle_stages); row-wise maximum by default."""
+    metric = metric or row_rel_err
     out = {}
     if n_streams > 1 and "u" in got:
-        out["u"] = row_rel_err(got["u"], ref["u"])
+        out["u"] = metric(got["u"], ref["u"])
     if rotated_qk:
-        out["q"] = row_rel_err(got["q"], ref["q"])
-        out["k"] = row_rel_err(got["k"], ref["k"])
-    out["v"] = row_rel_err(got["v"], ref["v"])
+        out["q"] = metric(got["q"], ref["q"])
+        out["k"] = metric(got["k"], ref["k"])
+    out["v"] = metric(got["v"], ref["v"])
     for key in ("attn", "a", "m"):
-        out[key] = row_rel_err(got[key], ref[key])
+        out[key] = metric(got[key], ref[key])
     return out
 
 
 def tolerances() -> Dict[str, float]:
     return {"u": TOL_U, "q": TOL_STAGE, "k": TOL_STAGE, "v": TOL_STAGE, "attn": TOL_ATTN, "a": TOL_ATTN, "m": TOL_STAGE}
+
+
+def tolerances_rounded() -> Dict[str, float]:
+    """Bounds on the relative Frobenius error of a stage against the oracle run with round_bf16 (operands rounded to
+    bf16 where the kernels round them).  q, k and v then differ only where fp32 and fp64 accumulation fall on two sides
+    of a rounding boundary (observed: 0 to 2e-4), which makes this the tight check of the projection, the rotation
+    and the norm.  The heads' outputs stay at 2e-3..4e-3: the kernels round the probabilities relative to a running
+    reference exponent, which no oracle can reproduce, and the output's own bf16 rounding then differs by whole ulps."""
+    return {"u": TOL_U, "q": 5e-4, "k": 5e-4, "v": 5e-4, "attn": 6e-3, "a": 6e-3, "m": 4e-3}
 
 
 def model_of(case: StageCase, t: Dict[str, np.ndarray]) -> oc.Model:

@@ -435,6 +435,50 @@ def test_iterate_calls_compose():
     assert np.array_equal(c, tr0) and pc.shape == (0, 2, shp.L)
 
 
+# ---------------------------------------------------------------- the bf16-operand test aid
+
+def test_bf16_rounding_aid_matches_torch_and_changes_no_formula():
+    """round_bf16 only rounds stored operands: bf16_round is torch's float32 -> bfloat16 conversion; the rounded branch
+    equals the same composition written with torch bfloat16 casts; switched off, nothing changes."""
+    rng = np.random.default_rng(9)
+    x = np.concatenate([rng.standard_normal(4096) * 10.0 ** rng.integers(-6, 6, 4096), [0.0, -0.0, 1.0, 3.0e38, 1.0e-40]])
+    want = torch.from_numpy(x.astype(np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(oc.bf16_round(x), want)
+    assert np.array_equal(oc.bf16_round(x), si.bf16_bits_to_f32(si.f32_to_bf16_bits(x.astype(np.float32))).astype(np.float64))
+
+    shp, t, md = small(P=3, L=2, T=5, B=1)
+    u = t["h0"][:, 0, :].astype(np.float64)
+    exact_a, exact_m = oc.branch(md, 1, u)
+    mdr = oc.Model(**{**md.__dict__, "round_bf16": True})
+    ra, rm = oc.branch(mdr, 1, u)
+    assert 1e-4 < rel_err(ra, exact_a) < 2e-2 and 1e-4 < rel_err(rm, exact_m) < 2e-2      # operand rounding only
+    bf = lambda z: z.to(torch.bfloat16).to(torch.float64)
+    tt = lambda z: torch.from_numpy(np.ascontiguousarray(z, dtype=np.float64))
+    eps, dh, H, T = md.rms_eps, md.head_dim, md.n_heads, md.T
+    norm = lambda z: z / torch.sqrt((z * z).mean(-1, keepdim=True) + eps)
+    xh = bf(norm(tt(u)).float())
+    qkv = bf((xh @ tt(md.Wqkv[0])).float()).reshape(T, 3, H, dh)
+    cos, sin = [tt(z) for z in oc.rope_cos_sin(md.P + np.arange(T), dh, md.rope_base)]
+    def rot(z):                                                   # z [T, H, dh]
+        z1, z2 = z[..., : dh // 2], z[..., dh // 2:]
+        return torch.cat([z1 * cos[:, None] - z2 * sin[:, None], z2 * cos[:, None] + z1 * sin[:, None]], -1)
+    q = bf(norm(rot(qkv[:, 0])).float()).transpose(0, 1)         # [H, T, dh]
+    k = bf(norm(rot(qkv[:, 1])).float()).transpose(0, 1)
+    v = qkv[:, 2].transpose(0, 1)
+    keys = torch.cat([tt(md.Kpre[0][0]), k], 1)
+    vals = torch.cat([tt(md.Vpre[0][0]), v], 1)
+    sc = q @ keys.transpose(1, 2) / np.sqrt(dh)
+    vis = torch.cat([torch.ones(T, md.P, dtype=torch.bool), torch.tril(torch.ones(T, T, dtype=torch.bool))], 1)
+    sc = sc.masked_fill(~vis, float("-inf"))
+    e = torch.exp(sc - sc.max(-1, keepdim=True).values)
+    o = bf(((bf(e.float()) @ vals) / e.sum(-1, keepdim=True)).float()).transpose(0, 1).reshape(T, H * dh)
+    a = o @ tt(md.Wo[0])
+    assert rel_err(ra, a.numpy()) < 1e-12
+    x2 = bf(norm(tt(u) + a).float())
+    hid = bf((torch.relu(x2 @ tt(md.Wfc[0])) ** 2).float())
+    assert rel_err(rm, (hid @ tt(md.Wproj[0])).numpy()) < 1e-12
+
+
 # ---------------------------------------------------------------- the pins notice planted mistakes
 
 def _pins_hold(mod) -> bool:
