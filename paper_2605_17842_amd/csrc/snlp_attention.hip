@@ -82,6 +82,8 @@ constexpr int kDh = 128;
 constexpr int kTile = 32;            // keys per tile
 constexpr int kKRow = kDh + 8;       // LDS row of a K tile (elements): 272 B
 constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kNoRef = -1.0e30f;   // reference exponent of a softmax state that has seen no visible key yet (finite:
+                                     // differences and products with it stay free of inf - inf)
 
 
 // Where key kk of (layer li, sequence b, head h) lives: prefix row or this block's row; keys past the end
@@ -117,6 +119,7 @@ __device__ __forceinline__ void attn_tile(const bf16x8_t (&kf)[2][4], const bf16
   const int kb = lane >> 4;
   const bool all_visible = tile_base + kTile <= min_limit;   // uniform: no masking needed in this tile
   bf16x8_t pf[QF];
+  float sv[QF][8];     // raw scores q.k of this lane's 8 keys
 #pragma unroll
   for (int f = 0; f < QF; ++f) {
     f32x4_t s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
@@ -125,40 +128,62 @@ __device__ __forceinline__ void attn_tile(const bf16x8_t (&kf)[2][4], const bf16
       s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[0][s], qf[f][s], s0, 0, 0, 0);
       s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[1][s], qf[f][s], s1, 0, 0, 0);
     }
-    float sv[8];   // raw scores q.k of this lane's 8 keys
 #pragma unroll
-    for (int i = 0; i < 4; ++i) { sv[i] = s0[i]; sv[4 + i] = s1[i]; }
-    if (!all_visible) {
+    for (int i = 0; i < 4; ++i) { sv[f][i] = s0[i]; sv[f][4 + i] = s1[i]; }
+  }
+  if (!all_visible) {
+#pragma unroll
+    for (int f = 0; f < QF; ++f)
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int k0 = tile_base + kb * 4 + i;
-        if (k0 >= limit[f]) sv[i] = -INFINITY;
-        if (k0 + 16 >= limit[f]) sv[4 + i] = -INFINITY;
+        if (k0 >= limit[f]) sv[f][i] = -INFINITY;
+        if (k0 + 16 >= limit[f]) sv[f][4 + i] = -INFINITY;
       }
-    }
-    float mloc = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])), fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
-    mloc = fmaxf(mloc, __shfl_xor(mloc, 16, kWave));
-    mloc = fmaxf(mloc, __shfl_xor(mloc, 32, kWave));
-    mloc *= scale_log2;                                       // scale > 0: max commutes with it
-    // st.m is the reference exponent of everything accumulated so far.  It follows the running maximum
-    // lazily: it is raised only when the maximum exceeds it by more than 2^8, so probabilities stay below
-    // 256 (exact enough in fp32 sums and in bf16) and the rescale of O and l is skipped in most tiles.
-    const bool raise = mloc > st.m[f] + 8.0f;
-    if (__builtin_amdgcn_ballot_w64(raise) != 0) {            // uniform branch
-      const float m_new = raise ? mloc : st.m[f];
-      const float alpha = exp2f(st.m[f] - ((m_new == -INFINITY) ? 0.f : m_new));
+  }
+  // st.m is the reference exponent of everything accumulated so far (kNoRef before the first visible key).  It
+  // follows the running maximum lazily: it is raised only when the maximum exceeds it by more than 2^8, so
+  // probabilities stay below 256 (exact enough in fp32 sums and in bf16) and the rescale of O and l is skipped in most
+  // tiles.  A column's maximum exceeds the bound exactly when one of its four lanes sees an exponent above 8, so the
+  // common case needs no exchange between lanes: the column maxima are formed only inside the rare branch.
+  float y[QF][8];      // exponents: score * scale * log2(e) - reference
+  bool over = false;
+#pragma unroll
+  for (int f = 0; f < QF; ++f) {
+    const float neg_m = -st.m[f];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) y[f][j] = fmaf(sv[f][j], scale_log2, neg_m);
+    const float ymax = fmaxf(fmaxf(fmaxf(y[f][0], y[f][1]), fmaxf(y[f][2], y[f][3])),
+                             fmaxf(fmaxf(y[f][4], y[f][5]), fmaxf(y[f][6], y[f][7])));
+    over = over || (ymax > 8.0f);
+  }
+  if (__builtin_amdgcn_ballot_w64(over) != 0) {               // uniform branch
+#pragma unroll
+    for (int f = 0; f < QF; ++f) {
+      float mcol = fmaxf(fmaxf(fmaxf(sv[f][0], sv[f][1]), fmaxf(sv[f][2], sv[f][3])),
+                         fmaxf(fmaxf(sv[f][4], sv[f][5]), fmaxf(sv[f][6], sv[f][7]))) * scale_log2;   // scale > 0
+      mcol = fmaxf(mcol, __shfl_xor(mcol, 16, kWave));
+      mcol = fmaxf(mcol, __shfl_xor(mcol, 32, kWave));
+      const float m_new = mcol > st.m[f] + 8.0f ? mcol : st.m[f];
+      const float alpha = __builtin_amdgcn_exp2f(st.m[f] - m_new);
       st.m[f] = m_new;
       st.l[f] *= alpha;
 #pragma unroll
       for (int mt = 0; mt < 8; ++mt) {
         st.o[f][mt][0] *= alpha; st.o[f][mt][1] *= alpha; st.o[f][mt][2] *= alpha; st.o[f][mt][3] *= alpha;
       }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) y[f][j] = fmaf(sv[f][j], scale_log2, -m_new);
     }
-    const float neg_m = (st.m[f] == -INFINITY) ? 0.f : -st.m[f];
+  }
+  // probabilities: the hardware's base-2 exponential (results below 2^-126 become zero, which is what they are
+  // worth; a masked score is -inf and gives exactly 0)
+#pragma unroll
+  for (int f = 0; f < QF; ++f) {
     float psum = 0.f;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      const float p = exp2f(fmaf(sv[j], scale_log2, neg_m));
+      const float p = __builtin_amdgcn_exp2f(y[f][j]);
       psum += p;
       pf[f][j] = static_cast<__bf16>(p);
     }
@@ -226,7 +251,8 @@ __global__ __launch_bounds__(kThreads, 2) void k_attn_bf16_block(const bf16_t* _
   const int li = l0 - 1 + blockIdx.y;            // 0-based layer
   const int b = blockIdx.x / H, h = blockIdx.x % H;
   const int q0 = (gridDim.z - 1 - blockIdx.z) * 128;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform over the wave: keeps what depends on it scalar
   const int kb = lane >> 4;
   const size_t blk_stride = (size_t)3 * d;
   const bf16_t* qkv_b = qkv + ((size_t)li * M + (size_t)b * T) * blk_stride;
@@ -256,7 +282,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_attn_bf16_block(const bf16_t* _
   SoftmaxState<QF> st;
 #pragma unroll
   for (int f = 0; f < QF; ++f) {
-    st.m[f] = -INFINITY; st.l[f] = 0.f;
+    st.m[f] = kNoRef; st.l[f] = 0.f;
 #pragma unroll
     for (int mt = 0; mt < 8; ++mt) st.o[f][mt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
   }
@@ -268,15 +294,39 @@ __global__ __launch_bounds__(kThreads, 2) void k_attn_bf16_block(const bf16_t* _
   const int wave_first = P + (q0 + wave * 32 < T ? q0 + wave * 32 : T - 1) + 1;        // keys visible to all its rows
   const float scale_log2 = kLog2e / sqrtf((float)kDh);
 
-  // wave w issues the 4-row groups g = 4w .. 4w+3 of the K tile and of the V tile
+  // wave w issues the 4-row groups g = w, w + 4, w + 8, w + 12 of the K tile and of the V tile (rows 16 j + 4 w + kb:
+  // the swizzle key row % 16 is then the same for a lane's four loads).  A tile that lies wholly in the prefix or
+  // wholly in the block (every tile when P = 0, up to the last one) has addresses that are linear in the tile index:
+  // a uniform base plus one per-lane offset that never changes; only a tile that straddles the two, or reaches past
+  // the last key, takes the per-row choice.
+  const int irow = wave * 4 + (lane >> 4);                          // row inside a 16-row group = its swizzle key
+  const int iswz = ((lane & 15) ^ irow) << 3;
+  const unsigned off_pre = (unsigned)(irow * kDh + iswz), off_blk = (unsigned)(irow * (int)blk_stride + iswz);
   auto issue = [&](bf16_t* sK, bf16_t* sV, int tile) {
     const int base = tile * kBTile;
+    if (base + kBTile <= P) {
+      const bf16_t* kp = src.kpre + (size_t)base * kDh;
+      const bf16_t* vp = src.vpre + (size_t)base * kDh;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int g = wave * 4 + j;
-      const int row = g * 4 + (lane >> 4), pos = lane & 15;
-      SNLP_GLDS16(src.k_row(base + row) + ((pos ^ (row & 15)) << 3), sK + g * (4 * kDh));
-      SNLP_GLDS16(src.v_row(base + row) + ((pos ^ (row & 15)) << 3), sV + g * (4 * kDh));
+      for (int j = 0; j < 4; ++j) {
+        SNLP_GLDS16(kp + (size_t)j * 16 * kDh + off_pre, sK + (wave + 4 * j) * (4 * kDh));
+        SNLP_GLDS16(vp + (size_t)j * 16 * kDh + off_pre, sV + (wave + 4 * j) * (4 * kDh));
+      }
+    } else if (base >= P && base + kBTile <= src.nkeys) {
+      const bf16_t* kp = src.kblk + (size_t)(base - P) * blk_stride;
+      const bf16_t* vp = src.vblk + (size_t)(base - P) * blk_stride;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        SNLP_GLDS16(kp + (size_t)j * 16 * blk_stride + off_blk, sK + (wave + 4 * j) * (4 * kDh));
+        SNLP_GLDS16(vp + (size_t)j * 16 * blk_stride + off_blk, sV + (wave + 4 * j) * (4 * kDh));
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int row = j * 16 + irow;
+        SNLP_GLDS16(src.k_row(base + row) + iswz, sK + (wave + 4 * j) * (4 * kDh));
+        SNLP_GLDS16(src.v_row(base + row) + iswz, sV + (wave + 4 * j) * (4 * kDh));
+      }
     }
   };
   auto compute = [&](const bf16_t* sK, const bf16_t* sV, int tile) {
@@ -404,7 +454,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_attn_bf16_decode(const bf16_t* 
     if (cos_tab) rope_qknorm_frags(qf[0], cos_tab + (size_t)t * (kDh / 2), sin_tab + (size_t)t * (kDh / 2), kb, eps);
   }
   SoftmaxState<QF> st;
-  st.m[0] = -INFINITY; st.l[0] = 0.f;
+  st.m[0] = kNoRef; st.l[0] = 0.f;
 #pragma unroll
   for (int mt = 0; mt < 8; ++mt) st.o[0][mt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
