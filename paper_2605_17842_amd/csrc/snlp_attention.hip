@@ -3,16 +3,17 @@
 // this block's rows t' <= t], q/k/v being the (rotated, normalised) thirds of qkv[l] and the prefix the
 // read-only cache of layer l.  (Attn_l(Q_l h, K_l h, V_l h) of the Appendix "Fused Cross-Layer Coupling".)
 //
-// bf16 path (head_dim 128): v_mfma_f32_16x16x32_bf16 on TRANSPOSED products so that a lane owns one
-// query column in both S^T = K Q^T and O^T = V^T P^T: the softmax statistics and the rescaling of O are
-// lane-local, and the probabilities leave the S^T accumulators already in the operand layout of the
-// second product.  V tiles sit in LDS as loaded ([key][dh], chunk-swizzled); the V^T operand comes out of
-// them with the LDS transpose read (ds_read_b64_tr_b16); online softmax in fp32 (base 2).
-//   * block kernel (any T): a workgroup owns 128 query rows, its 4 waves 32 each, sharing K / V tiles of 64
-//     keys that arrive by direct-to-LDS loads, double-buffered.
+// bf16 path (head_dim 128): MFMAs on TRANSPOSED products so that a lane owns one query column in both
+// S^T = K Q^T and O^T = V^T P^T: the softmax statistics and the rescaling of O are lane-local, and the
+// probabilities leave the S^T accumulators already in the operand layout of the second product.  V tiles sit
+// in LDS as loaded ([key][dh], chunk-swizzled); the V^T operand comes out of them with the LDS transpose read
+// (ds_read_b64_tr_b16); online softmax in fp32 (base 2, the hardware exponential).
+//   * block kernel (T > 16): a workgroup owns 128 query rows, its 4 waves 32 each (v_mfma_f32_32x32x16_bf16),
+//     sharing K / V steps of 32 keys that arrive by direct-to-LDS loads two steps ahead; three workgroups per
+//     compute unit.
 //   * decode kernel (T <= 16): a workgroup owns one (layer, sequence, head); its 4 waves split the key
-//     tiles, stream K straight into MFMA operand registers and V through wave-private LDS, and merge
-//     their partial softmax states in a fixed order.
+//     tiles (v_mfma_f32_16x16x32_bf16: 16 query columns are all a decode block has), stream K straight into MFMA
+//     operand registers and V through wave-private LDS, and merge their partial softmax states in a fixed order.
 // Results for a (layer, b, h) never depend on how many layers are in the launch.
 #include "snlp_kernels.hpp"
 
@@ -227,151 +228,269 @@ __device__ __forceinline__ uint2 pack4_bf16(float a, float b, float c, float d) 
   return r;
 }
 
-// ---- block kernel: grid (B * H, Lc, ceil(T / 128)); query tiles are dispatched last-first: under the causal
-// mask the last tile has the most keys, and starting the long workgroups first shortens the tail
-// K and V tiles of 64 keys travel global -> LDS with direct-to-LDS loads (lane i's 16 bytes land at base + 16 i),
-// two stages: tile i+1 is in flight while tile i is consumed.  K and V rows (256 B) are stored with their
-// 16-byte chunk c at position c ^ (row & 15) so that the 16 rows of an operand read (K) or of a transpose read
-// (V) spread over all banks; the permutation is applied on the global-address side.
+// ---- block kernel: 1-D grid over (stream, query tile); a stream's query tiles are dispatched last-first: under the
+// causal mask the last tile has the most keys, and starting the long workgroups first shortens the tail.
+// 4 waves per workgroup, 32 query rows per wave, keys in steps of 32, both products with
+// v_mfma_f32_32x32x16_bf16 on transposed operands: S^T (32 keys x 32 queries) = K Q^T over 8 k-steps of 16 channels,
+// O^T (128 channels x 32 queries, four 32-row tiles) += V^T P^T over 2 k-steps of 16 keys.  A lane owns one query
+// column in both (its 32 keys of a step are shared with lane ^ 32), so the softmax statistics are lane-local and the
+// probabilities leave the S^T accumulator already in the operand layout of the second product.
+// What limits this kernel is the latency of a wave's own instruction stream: a step is a chain (K operand reads,
+// eight dependent MFMAs, ~90 VALU instructions of softmax -- a lone wave issues one VALU instruction per ~10
+// cycles, measured -- the V reads, eight more MFMAs) of ~2000 cycles, of which the matrix pipe is busy 512.  So the
+// kernel is built for THREE workgroups per compute unit (3 waves per SIMD): 168 registers, 48 KB of LDS.
+// K and V travel global -> LDS with direct-to-LDS loads (lane i's 16 bytes land at base + 16 i) into two rings of
+// three 32-row slots each: step j lives in slot j % 3.  Rows are 256 B, stored with their 16-byte chunk c at
+// position c ^ swz(row % 16), swz = the row's two low bits exchanged with its two high bits, applied on the
+// global-address side: the 16 rows of a K operand read then spread over all banks, and so do the 4 rows x 4 chunks
+// that one half-wave touches in a transpose read of V.
+// One barrier per step: in step j the waves read slot j % 3 and request the rows of step j + 2 into the slot that
+// step j - 1 left.  Every step requests the same number of rows (past the last key: the last key again, into rows
+// nobody reads), so that "all but the loads of the last step have landed" is one constant wait count.
+// The load is written out instead of taken from the builtin: the compiler makes every LDS read that follows a
+// direct-to-LDS load it knows of wait for ALL outstanding loads (it cannot tell ring rows apart), which would
+// cancel the prefetch -- every step would begin by waiting for the rows just requested.  The waits are explicit
+// here: one counted s_waitcnt before the barrier of each phase.  m0 carries the LDS base of the wave's 1 KB.
 #define SNLP_GLDS16(gptr, lptr)                                                                              \
-  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gptr),                   \
-                                   (__attribute__((address_space(3))) void*)(lptr), 16, 0, 0)
-constexpr int kBTile = 64;            // keys per stage
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"                               \
+               :: "v"(gptr), "s"((uint32_t)(size_t)((__attribute__((address_space(3))) char*)(lptr)))        \
+               : "memory", "m0")
 
-__global__ __launch_bounds__(kThreads, 2) void k_attn_bf16_block(const bf16_t* __restrict__ qkv,
-                                                                  const bf16_t* __restrict__ Kpre,
-                                                                  const bf16_t* __restrict__ Vpre,
-                                                                  bf16_t* __restrict__ out, int l0, int M, int T, int P,
-                                                                  int B, int H, int d) {
-  constexpr int QF = 2;
-  __shared__ __attribute__((aligned(16))) bf16_t sK0[kBTile * kDh];
-  __shared__ __attribute__((aligned(16))) bf16_t sK1[kBTile * kDh];
-  __shared__ __attribute__((aligned(16))) bf16_t sV0[kBTile * kDh];
-  __shared__ __attribute__((aligned(16))) bf16_t sV1[kBTile * kDh];
-  const int li = l0 - 1 + blockIdx.y;            // 0-based layer
-  const int b = blockIdx.x / H, h = blockIdx.x % H;
-  const int q0 = (gridDim.z - 1 - blockIdx.z) * 128;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+
+__device__ __forceinline__ int ring_swz(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
+
+__global__ __launch_bounds__(256, 3) void k_attn_bf16_block(const bf16_t* __restrict__ qkv,
+                                                            const bf16_t* __restrict__ Kpre,
+                                                            const bf16_t* __restrict__ Vpre,
+                                                            bf16_t* __restrict__ out, int l0, int M, int T, int P, int B,
+                                                            int H, int d, int n_streams, int n_qtiles, int stream_major) {
+  constexpr int kSlots = 3;                     // 32-row slots of the K ring and of the V ring
+  constexpr int kRing = kSlots * kTile;
+  constexpr int kDepth = kSlots - 1;            // steps between the request of a row and its use
+  constexpr int kRowsWg = 128;                  // query rows per workgroup
+  constexpr int kLoadsPerStep = 4;              // per wave: 32 K rows and 32 V rows, 4 rows per load, over 4 waves
+  __shared__ __attribute__((aligned(16))) bf16_t sK[kRing * kDh];
+  __shared__ __attribute__((aligned(16))) bf16_t sV[kRing * kDh];
+  // Workgroup -> (stream = (layer, sequence, head), query tile), heaviest query tile first.
+  // Long blocks (stream_major): workgroups are handed to the 8 XCDs in turn (workgroup n runs on XCD n % 8) and each
+  // XCD has its own L2, so the query tiles of one stream are given consecutive places on ONE XCD: they start
+  // together, walk the same K / V rows at the same pace and all but the first read them from that L2.
+  // Short blocks: all streams' heaviest tiles first, then the next ones; with few tiles per stream the order that
+  // balances the tail is worth more than the sharing.
+  int stream, qtile;
+  if (stream_major) {
+    const unsigned xcd = blockIdx.x & 7, in_xcd = blockIdx.x >> 3;
+    stream = (int)(in_xcd / (unsigned)n_qtiles) * 8 + (int)xcd;
+    qtile = n_qtiles - 1 - (int)(in_xcd % (unsigned)n_qtiles);
+  } else {
+    stream = (int)(blockIdx.x % (unsigned)n_streams);
+    qtile = n_qtiles - 1 - (int)(blockIdx.x / (unsigned)n_streams);
+  }
+  if (stream >= n_streams) return;               // whole workgroup (stream-major: the last group of 8 may be short)
+  const int li = l0 - 1 + stream / (B * H);      // 0-based layer
+  const int b = (stream % (B * H)) / H, h = stream % H;
+  const int q0 = qtile * kRowsWg;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform over the wave: keeps what depends on it scalar
-  const int kb = lane >> 4;
+  const int l32 = lane & 31, hi = lane >> 5;
   const size_t blk_stride = (size_t)3 * d;
   const bf16_t* qkv_b = qkv + ((size_t)li * M + (size_t)b * T) * blk_stride;
+  const int nkeys = P + T;
+  const bf16_t* kpre = Kpre ? Kpre + (((size_t)li * B + b) * H + h) * (size_t)P * kDh : nullptr;
+  const bf16_t* vpre = Vpre ? Vpre + (((size_t)li * B + b) * H + h) * (size_t)P * kDh : nullptr;
+  const bf16_t* kblk = qkv_b + d + (size_t)h * kDh;
+  const bf16_t* vblk = qkv_b + 2 * d + (size_t)h * kDh;
 
-  KvSource src;
-  src.P = P; src.nkeys = P + T; src.blk_stride = blk_stride;
-  src.kpre = Kpre ? Kpre + (((size_t)li * B + b) * H + h) * (size_t)P * kDh : nullptr;
-  src.vpre = Vpre ? Vpre + (((size_t)li * B + b) * H + h) * (size_t)P * kDh : nullptr;
-  src.kblk = qkv_b + d + (size_t)h * kDh;
-  src.vblk = qkv_b + 2 * d + (size_t)h * kDh;
-
-  // query fragments straight from global memory in operand layout
-  bf16x8_t qf[QF][4];
-  int limit[QF];
-  int trow[QF];
+  // Q operand (B of the first product) straight from global memory: column = query lane % 32, k-step ks holds channels
+  // 16 ks + 8 (lane / 32) .. + 7
+  const int trow = q0 + wave * 32 + l32;
+  const int tq = trow < T ? trow : T - 1;
+  const int limit = P + tq + 1;                  // number of keys visible to this lane's query
+  bf16x8_t qf[8];
+  {
+    const bf16_t* qp = qkv_b + (size_t)tq * blk_stride + (size_t)h * kDh + hi * 8;
 #pragma unroll
-  for (int f = 0; f < QF; ++f) {
-    int t = q0 + wave * 32 + f * 16 + (lane & 15);
-    trow[f] = t;
-    t = t < T ? t : T - 1;
-    limit[f] = P + t + 1;
-    const bf16_t* qp = qkv_b + (size_t)t * blk_stride + (size_t)h * kDh;
-#pragma unroll
-    for (int s = 0; s < 4; ++s) qf[f][s] = *reinterpret_cast<const bf16x8_t*>(qp + s * 32 + kb * 8);
+    for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const bf16x8_t*>(qp + ks * 16);
   }
 
-  SoftmaxState<QF> st;
+  f32x16_t o[4];      // O^T tile dt: channels 32 dt + 8 (r / 4) + 4 (lane / 32) + r % 4 of query lane % 32
+  float mref = kNoRef;   // reference exponent (kNoRef before the first visible key), equal in lanes l and l ^ 32
+  float lsum = 0.f;      // running sum of this lane's own keys
 #pragma unroll
-  for (int f = 0; f < QF; ++f) {
-    st.m[f] = kNoRef; st.l[f] = 0.f;
+  for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-    for (int mt = 0; mt < 8; ++mt) st.o[f][mt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-  }
+    for (int r = 0; r < 16; ++r) o[dt][r] = 0.f;
 
-  const int q_last = (q0 + 127 < T ? q0 + 127 : T - 1);
+  const int q_last = (q0 + kRowsWg - 1 < T ? q0 + kRowsWg - 1 : T - 1);
   const int nkeys_wg = P + q_last + 1;                       // keys visible to the last row of the workgroup
-  const int ntiles = (nkeys_wg + kBTile - 1) / kBTile;
+  const int nsteps = (nkeys_wg + kTile - 1) / kTile;
   const int wave_last = P + (q0 + wave * 32 + 31 < T ? q0 + wave * 32 + 31 : T - 1);   // last key this wave can see
   const int wave_first = P + (q0 + wave * 32 < T ? q0 + wave * 32 : T - 1) + 1;        // keys visible to all its rows
+  const int nsteps_w = wave_last / kTile + 1;                // steps this wave takes part in
   const float scale_log2 = kLog2e / sqrtf((float)kDh);
 
-  // wave w issues the 4-row groups g = w, w + 4, w + 8, w + 12 of the K tile and of the V tile (rows 16 j + 4 w + kb:
-  // the swizzle key row % 16 is then the same for a lane's four loads).  A tile that lies wholly in the prefix or
-  // wholly in the block (every tile when P = 0, up to the last one) has addresses that are linear in the tile index:
-  // a uniform base plus one per-lane offset that never changes; only a tile that straddles the two, or reaches past
-  // the last key, takes the per-row choice.
-  const int irow = wave * 4 + (lane >> 4);                          // row inside a 16-row group = its swizzle key
-  const int iswz = ((lane & 15) ^ irow) << 3;
-  const unsigned off_pre = (unsigned)(irow * kDh + iswz), off_blk = (unsigned)(irow * (int)blk_stride + iswz);
-  auto issue = [&](bf16_t* sK, bf16_t* sV, int tile) {
-    const int base = tile * kBTile;
-    if (base + kBTile <= P) {
-      const bf16_t* kp = src.kpre + (size_t)base * kDh;
-      const bf16_t* vp = src.vpre + (size_t)base * kDh;
+  // Loads.  A step's 32 rows are 8 groups of 4 rows; wave w fetches groups w and w + 4 with one instruction each
+  // (lane = 16 (row - 4 g) + chunk position), so a lane's row % 16, and with it the swizzle key, is the same in both.
+  // A step that lies wholly in the prefix or wholly in the block (every step when P = 0, up to the last one) has
+  // addresses linear in the step index: a uniform pointer plus one per-lane offset that never changes; a step that
+  // straddles the two, or reaches past the last key, chooses per row (rows past the end repeat the last key; their
+  // probabilities are masked to zero).
+  const int lrow = wave * 4 + (lane >> 4);                       // row of the first group this lane fetches
+  const int iswz = ((lane & 15) ^ ring_swz(lrow)) << 3;
+  const unsigned off_pre = (unsigned)(lrow * kDh + iswz), off_blk = (unsigned)(lrow * (int)blk_stride + iswz);
+  auto load_step = [&](bf16_t* ring, const bf16_t* pre, const bf16_t* blk, int j, int slot) {
+    const int base = j * kTile;
+    bf16_t* dst = ring + (slot * kTile + wave * 4) * kDh;           // + 16 B per lane, by the instruction
+    if (base + kTile <= P) {
+      const bf16_t* p0 = pre + (size_t)base * kDh;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        SNLP_GLDS16(kp + (size_t)j * 16 * kDh + off_pre, sK + (wave + 4 * j) * (4 * kDh));
-        SNLP_GLDS16(vp + (size_t)j * 16 * kDh + off_pre, sV + (wave + 4 * j) * (4 * kDh));
-      }
-    } else if (base >= P && base + kBTile <= src.nkeys) {
-      const bf16_t* kp = src.kblk + (size_t)(base - P) * blk_stride;
-      const bf16_t* vp = src.vblk + (size_t)(base - P) * blk_stride;
+      for (int g = 0; g < 2; ++g) SNLP_GLDS16(p0 + (size_t)g * 16 * kDh + off_pre, dst + g * 16 * kDh);
+    } else if (base >= P && base + kTile <= nkeys) {
+      const bf16_t* p0 = blk + (size_t)(base - P) * blk_stride;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        SNLP_GLDS16(kp + (size_t)j * 16 * blk_stride + off_blk, sK + (wave + 4 * j) * (4 * kDh));
-        SNLP_GLDS16(vp + (size_t)j * 16 * blk_stride + off_blk, sV + (wave + 4 * j) * (4 * kDh));
-      }
+      for (int g = 0; g < 2; ++g) SNLP_GLDS16(p0 + (size_t)g * 16 * blk_stride + off_blk, dst + g * 16 * kDh);
     } else {
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int row = j * 16 + irow;
-        SNLP_GLDS16(src.k_row(base + row) + iswz, sK + (wave + 4 * j) * (4 * kDh));
-        SNLP_GLDS16(src.v_row(base + row) + iswz, sV + (wave + 4 * j) * (4 * kDh));
-      }
-    }
-  };
-  auto compute = [&](const bf16_t* sK, const bf16_t* sV, int tile) {
-#pragma unroll
-    for (int sub = 0; sub < 2; ++sub) {
-      const int tb = tile * kBTile + sub * kTile;
-      if (tb <= wave_last) {   // uniform over the wave
-        bf16x8_t kf[2][4];
-#pragma unroll
-        for (int tau = 0; tau < 2; ++tau)
-#pragma unroll
-          for (int s = 0; s < 4; ++s)
-            kf[tau][s] = *reinterpret_cast<const bf16x8_t*>(sK + (sub * 32 + tau * 16 + (lane & 15)) * kDh +
-                                                            (((s * 4 + kb) ^ (lane & 15)) << 3));
-        attn_tile<QF>(kf, qf, sV + sub * kTile * kDh, tb, limit, wave_first, scale_log2, st, lane);
+      for (int g = 0; g < 2; ++g) {
+        int kk = base + g * 16 + lrow;
+        kk = kk < nkeys ? kk : nkeys - 1;
+        const bf16_t* rp = kk < P ? pre + (size_t)kk * kDh : blk + (size_t)(kk - P) * blk_stride;
+        SNLP_GLDS16(rp + iswz, dst + g * 16 * kDh);
       }
     }
   };
 
-  issue(sK0, sV0, 0);
-  for (int it = 0; it < ntiles; it += 2) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's part of tile `it` has landed
-    __syncthreads();                                    // everyone's has; everyone is done with the other stage
-    if (it + 1 < ntiles) issue(sK1, sV1, it + 1);
-    compute(sK0, sV0, it);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (it + 2 < ntiles) issue(sK0, sV0, it + 2);
-    if (it + 1 < ntiles) compute(sK1, sV1, it + 1);
+  // Operand reads (element offsets inside a step's 32 ring rows).
+  // K (A of the first product): row = key lane % 32, k-step ks = chunk 2 ks + lane / 32.
+  // V^T (A of the second product), channel tile dt, key step kk: row = channel 32 dt + lane % 32, and k slot e of
+  // lane half hi stands for key 16 kk + 8 (e / 4) + 4 hi + e % 4 -- the key whose probability the lane holds in
+  // accumulator element 8 kk + e.  It comes from the row-major V rows with the LDS transpose read: in each group
+  // of 16 lanes, lane s supplies the address of 4 consecutive 16-bit elements and lane i receives element i % 4 of
+  // the rows addressed by lanes i / 4, 4 + i / 4, 8 + i / 4, 12 + i / 4.  So lane s addresses key row s / 4 of the
+  // four keys 16 kk + 4 hi + 0..3 at channel 32 dt + 16 (lane / 16 % 2) + 4 (s % 4), and lane i receives those four
+  // keys at channel 32 dt + lane % 32; a second read 8 rows further on gives slots 4..7.
+  int koff[8];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) koff[ks] = l32 * kDh + (((2 * ks + hi) ^ ring_swz(l32 & 15)) << 3);
+  const int i16 = lane & 15;
+  const int vrow = 4 * hi + (i16 >> 2);                          // + 16 kk (+ 8 for the second read): same swizzle key
+  int voff[4];
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+    voff[dt] = vrow * kDh + ((i16 & 1) << 2) + (((4 * dt + 2 * ((lane >> 4) & 1) + ((i16 & 3) >> 1)) ^ ring_swz(vrow)) << 3);
+  const int vswz8 = ring_swz(vrow) ^ ring_swz(vrow + 8);         // what 8 rows further on changes in the position
+
+  // One step: the 32 keys of step j, from ring slot `slot`.
+  auto step = [&](int j, int slot) {
+    const bf16_t* kr = sK + slot * (kTile * kDh);
+    const bf16_t* vr = sV + slot * (kTile * kDh);
+    f32x16_t sacc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(kr + koff[ks]);
+      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc, 0, 0, 0);
+    }
+    // element r of the accumulator: key 32 j + 8 (r / 4) + 4 hi + r % 4
+    float sv[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sv[r] = sacc[r];
+    if ((j + 1) * kTile > wave_first) {                            // uniform: some row of the wave cannot see the whole step
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        if (j * kTile + 8 * (r >> 2) + 4 * hi + (r & 3) >= limit) sv[r] = -INFINITY;
+    }
+    // exponents relative to the reference.  The reference follows the running maximum lazily: it is raised only
+    // when the maximum exceeds it by more than 2^8, so probabilities stay below 256 (exact enough in fp32 sums and
+    // in bf16) and the rescale of O and l is skipped in most steps.  A column's maximum exceeds the bound exactly
+    // when one of its two lanes sees an exponent above 8, so the common case needs no exchange between lanes.
+    float y[16];
+    const float neg_m = -mref;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) y[r] = fmaf(sv[r], scale_log2, neg_m);
+    float ymax = fmaxf(fmaxf(fmaxf(y[0], y[1]), fmaxf(y[2], y[3])), fmaxf(fmaxf(y[4], y[5]), fmaxf(y[6], y[7])));
+    ymax = fmaxf(ymax, fmaxf(fmaxf(fmaxf(y[8], y[9]), fmaxf(y[10], y[11])), fmaxf(fmaxf(y[12], y[13]), fmaxf(y[14], y[15]))));
+    if (__builtin_amdgcn_ballot_w64(ymax > 8.0f) != 0) {           // uniform branch, rare
+      float mcol = sv[0];
+#pragma unroll
+      for (int r = 1; r < 16; ++r) mcol = fmaxf(mcol, sv[r]);
+      mcol *= scale_log2;                                          // scale > 0: max commutes with it
+      mcol = fmaxf(mcol, __shfl_xor(mcol, 32, kWave));
+      const float m_new = mcol > mref + 8.0f ? mcol : mref;
+      const float alpha = __builtin_amdgcn_exp2f(mref - m_new);
+      mref = m_new;
+      lsum *= alpha;
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) y[r] = fmaf(sv[r], scale_log2, -m_new);
+    }
+    // probabilities: the hardware's base-2 exponential (results below 2^-126 become zero, which is what they are
+    // worth; a masked score is -inf and gives exactly 0)
+    bf16x8_t pf[2];
+    float psum = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const float pr = __builtin_amdgcn_exp2f(y[r]);
+      psum += pr;
+      pf[r >> 3][r & 7] = static_cast<__bf16>(pr);
+    }
+    lsum += psum;
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt) {
+        const bf16_t* va = vr + kk * 16 * kDh + voff[dt];
+        const v4i16_t r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4i16_t*)va);
+        const v4i16_t r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (__attribute__((address_space(3))) v4i16_t*)(vr + kk * 16 * kDh + 8 * kDh + (voff[dt] ^ (vswz8 << 3))));
+        const v8i16_t rr = __builtin_shufflevector(r0, r1, 0, 1, 2, 3, 4, 5, 6, 7);
+        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, rr), pf[kk], o[dt], 0, 0, 0);
+      }
+  };
+
+  // prologue: steps 0 .. D - 1
+#pragma unroll
+  for (int c = 0; c < kDepth; ++c) {
+    load_step(sK, kpre, kblk, c, c);
+    load_step(sV, vpre, vblk, c, c);
   }
+  // The query operand is consumed here, before the loop, so that the compiler's own wait for its loads stands here
+  // too: it does not count the direct-to-LDS loads, and a wait "for the query" inside the loop would in fact wait
+  // for the rows just requested.
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qf[ks]));
+  int slot = 0;                                              // slot of step j; step j + D goes to the slot before it
+  for (int j = 0; j < nsteps; ++j) {
+    // this wave's part of the rows of step j has landed (loads return in order; only those of the last D - 1 steps
+    // may still be on their way); after the barrier everyone's has, and everyone is done with the rows this step's
+    // loads replace.  (A bare barrier: __syncthreads() may also wait for every outstanding load.)
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((kDepth - 1) * kLoadsPerStep) : "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    const int slot_in = slot == 0 ? kSlots - 1 : slot - 1;
+    load_step(sK, kpre, kblk, j + kDepth, slot_in);
+    load_step(sV, vpre, vblk, j + kDepth, slot_in);
+    if (j < nsteps_w) step(j, slot);                         // uniform over the wave
+    slot = slot + 1 == kSlots ? 0 : slot + 1;
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the last phases' loads have landed before the LDS is given back
 
+  lsum += __shfl_xor(lsum, 32, kWave);
+  const float inv = 1.0f / lsum;
+  if (trow < T) {
+    bf16_t* op = out + ((size_t)li * M + (size_t)b * T + trow) * d + (size_t)h * kDh + 4 * hi;
 #pragma unroll
-  for (int f = 0; f < QF; ++f) {
-    float lt = st.l[f];
-    lt += __shfl_xor(lt, 16, kWave);
-    lt += __shfl_xor(lt, 32, kWave);
-    const float inv = 1.0f / lt;
-    if (trow[f] < T) {
-      bf16_t* op = out + ((size_t)li * M + (size_t)b * T + trow[f]) * d + (size_t)h * kDh;
+    for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-      for (int mt = 0; mt < 8; ++mt) {
-        const uint2 v = pack4_bf16(st.o[f][mt][0] * inv, st.o[f][mt][1] * inv, st.o[f][mt][2] * inv, st.o[f][mt][3] * inv);
-        *reinterpret_cast<uint2*>(op + mt * 16 + kb * 4) = v;
+      for (int g = 0; g < 4; ++g) {
+        const uint2 v = pack4_bf16(o[dt][4 * g] * inv, o[dt][4 * g + 1] * inv, o[dt][4 * g + 2] * inv, o[dt][4 * g + 3] * inv);
+        *reinterpret_cast<uint2*>(op + 32 * dt + 8 * g) = v;
       }
-    }
   }
 }
 
@@ -608,8 +727,11 @@ hipError_t launch_attention_bf16(hipStream_t s, const Dims& D, int l0, int Lc, c
     hipLaunchKernelGGL(k_attn_bf16_decode, grid, block, 0, s, qkv, Kpre, Vpre, out, l0, D.M, D.T, D.P, D.B, D.H, D.d, cos_tab, sin_tab,
                        D.eps);
   } else {
-    dim3 grid(D.B * D.H, Lc, (D.T + 127) / 128), block(kThreads);
-    hipLaunchKernelGGL(k_attn_bf16_block, grid, block, 0, s, qkv, Kpre, Vpre, out, l0, D.M, D.T, D.P, D.B, D.H, D.d);
+    const int n_streams = D.B * D.H * Lc, n_qtiles = (D.T + 127) / 128;
+    const int stream_major = n_qtiles >= 8 ? 1 : 0;       // a function of the block length alone
+    dim3 grid((unsigned)(stream_major ? (n_streams + 7) / 8 * 8 * n_qtiles : n_streams * n_qtiles)), block(256);
+    hipLaunchKernelGGL(k_attn_bf16_block, grid, block, 0, s, qkv, Kpre, Vpre, out, l0, D.M, D.T, D.P, D.B, D.H, D.d, n_streams,
+                       n_qtiles, stream_major);
   }
   return hipGetLastError();
 }

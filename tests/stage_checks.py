@@ -81,6 +81,10 @@ def small(name, **kw) -> si.Shape:
 SMALL_CASES = [
     StageCase("block_T200_P37", small("block_T200_P37", B=1, T=200, P=37, seed=901)),
     StageCase("block_T40_P0", small("block_T40_P0", T=40, seed=902)),
+    # 8 query tiles per stream: the stream-major workgroup order, a ragged last tile, a prefix that ends inside a key step
+    StageCase("block_T1000_P37", small("block_T1000_P37", B=1, T=1000, P=37, seed=911), layers=(2,), second_state=False),
+    # prefix and block both made of whole key steps (the linear-address load paths)
+    StageCase("block_T130_P96", small("block_T130_P96", T=130, P=96, seed=912)),
     StageCase("decode_T1_P0", small("decode_T1_P0", T=1, seed=903)),
     StageCase("decode_T5_P70", small("decode_T5_P70", B=3, T=5, P=70, seed=904)),
     # decode kernel with its own rotation of q and of the block's k rows (P >= 512, T <= 16)
