@@ -19,7 +19,7 @@ import torch
 
 import snlp_inputs as si
 from oracle import snlp_oracle as oc
-from helpers import oracle_model, per_layer_rel_err, rel_err
+from oracle.harness import oracle_model, per_layer_rel_err, rel_err
 
 pytestmark = pytest.mark.gpu
 
@@ -32,7 +32,7 @@ def say(msg):
 
 
 def run_case(shp, t, mode, Ks, tol, to_L=True, widen=True):
-    import gpu_helpers as gh
+    from paper_2605_17842_amd import harness as gh
     md = oracle_model(shp, t, widen=widen)
     m = gh.gpu_model(shp, t)
     Kmax = max(Ks)
@@ -98,7 +98,7 @@ def test_large_tile_gemm_ragged_rows():
 
 
 def test_config4_identity_mixing_equals_idn():
-    import gpu_helpers as gh
+    from paper_2605_17842_amd import harness as gh
     shp = si.config(4)
     t = si.generate(shp, identity_mixing=True)
     m = gh.gpu_model(shp, t)
@@ -119,7 +119,7 @@ def test_config4_identity_mixing_equals_idn():
 
 def test_config5_d26_reduced_block_every_K():
     """K = 1..26 at T = 512: states against the oracle, residual norm and deviation from the sequential trace."""
-    import gpu_helpers as gh
+    from paper_2605_17842_amd import harness as gh
     shp = si.config(5, T=512)
     t = si.generate(shp)
     md = oracle_model(shp, t, widen=True)
@@ -159,7 +159,7 @@ def test_config5_d26_reduced_block_every_K():
 
 @pytest.fixture(scope="module")
 def d26():
-    import gpu_helpers as gh
+    from paper_2605_17842_amd import harness as gh
     shp = si.config(5)
     t = si.generate(shp)
     st = {"shp": shp, "t": t, "md": oracle_model(shp, t, widen=False), "m": gh.gpu_model(shp, t)}

@@ -12,7 +12,7 @@ import torch
 
 import snlp_inputs as si
 from oracle import snlp_oracle as oc
-from helpers import oracle_model, per_layer_rel_err, rel_err
+from oracle.harness import oracle_model, per_layer_rel_err, rel_err
 
 pytestmark = pytest.mark.gpu
 
@@ -27,8 +27,8 @@ def say(msg):
 
 @pytest.fixture(scope="module")
 def gh():
-    import gpu_helpers
-    return gpu_helpers
+    from paper_2605_17842_amd import harness
+    return harness
 
 
 def np_trace(m):

@@ -14,7 +14,7 @@ import torch.nn.functional as F
 
 import snlp_inputs as si
 from oracle import snlp_oracle as oc
-from helpers import oracle_model, rel_err
+from oracle.harness import oracle_model, rel_err
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
