@@ -101,6 +101,16 @@ SMALL_CASES = [
     StageCase("hcn_n4_T33", small("hcn_n4_T33", T=33, n_streams=4, L=3, seed=909), distinct_streams=True),
 ]
 
+# Block lengths and prefix lengths around the block kernel's step (32 keys), query tile (128 rows) and load paths
+# (GPU test only; one layer each).
+def _edge(T, P, seed):
+    name = "block_T%d_P%d" % (T, P)
+    return StageCase(name, small(name, L=1, B=1, T=T, P=P, seed=seed), second_state=False)
+
+
+EDGE_CASES = [_edge(T, P, 920 + i) for i, (T, P) in enumerate([
+    (17, 0), (31, 1), (32, 32), (33, 31), (63, 64), (64, 33), (65, 95), (127, 0), (128, 64), (129, 63), (255, 1), (257, 160)])]
+
 # The benchmark workloads at full size (GPU test only).
 FULL_CASES = [
     StageCase("d20_decode_T8", si.config(3, T=8)),

@@ -87,6 +87,11 @@ def test_stage_parity_small_cases(case):
     run_stage_case(case)
 
 
+@pytest.mark.parametrize("case", sc.EDGE_CASES, ids=lambda c: c.name)
+def test_stage_parity_block_kernel_edges(case):
+    run_stage_case(case)
+
+
 @pytest.mark.parametrize("case", sc.FULL_CASES, ids=lambda c: c.name)
 def test_stage_parity_d20_workloads(case):
     run_stage_case(case)
