@@ -131,15 +131,47 @@ def main():
     def step():
         m.iterate(snlp.IDN, 1, probe)
 
-    # ---- timed region: W warmup, then exactly K steps; the attention stage (dominant kernel) carries
-    # HIP events on the same stream
+    def event_times_us(fn, warm, runs):
+        """Per-call durations from events recorded on the launch stream between consecutive calls (the queue stays
+        full; no synchronisation inside the series)."""
+        for _ in range(warm):
+            fn()
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(runs + 1)]
+        sync()
+        evs[0].record()
+        for i in range(runs):
+            fn()
+            evs[i + 1].record()
+        sync()
+        return np.array([evs[i].elapsed_time(evs[i + 1]) * 1e3 for i in range(runs)])
+
+    def percentiles(x):
+        return {"median_us": float(np.median(x)), "p10_us": float(np.percentile(x, 10)), "p90_us": float(np.percentile(x, 90)),
+                "mean_us": float(np.mean(x)), "runs": int(len(x))}
+
+    # the paper's timing protocol (Experiments, setup: 50 warm-up runs, 200 measured runs), per-step event times.  It
+    # runs first: the device's clocks need some tens of milliseconds of load to settle after the host-side set-up
+    # (the first 20 steps after an idle period measure ~2.5 % slow), and this run doubles as that load.
+    m.init_trace(m.h0)
+    protocol_run = percentiles(event_times_us(step, 50, 200))
+
+    # ---- timed region: W warmup, then exactly K steps.  The attention stage (dominant kernel) carries HIP events on
+    # the launch stream in every fourth of them: an event record between two launches keeps the second kernel from
+    # starting under the first one's tail (~4 us per record), which is the timed quantity's business, not the kernel's
     m.init_trace(m.h0)
     for _ in range(args.warmup):
         step()
     sync()
-    m.profile_stages(1 << 3)
+    m.profile_stages(0)
     m.profile_read()
-    t_iter = timed(step, args.steps, sync)
+    count = [0]
+
+    def timed_step():
+        m.profile_stages(1 << 3 if count[0] % 4 == 0 else 0)
+        count[0] += 1
+        step()
+
+    t_iter = timed(timed_step, args.steps, sync)
     ms_attn, n_attn = m.profile_read()
     m.profile_stages(0)
     attn_ms = ms_attn[3] / max(n_attn[3], 1)
@@ -162,26 +194,7 @@ def main():
              "iteration_hbm_floor_us": iter_bytes / (HBM_PEAK_GBS * 1e9) * 1e6,
              "iteration_frac_of_hbm_floor": (iter_bytes / (HBM_PEAK_GBS * 1e9)) / t_iter}
 
-    def event_times_us(fn, warm, runs):
-        """Per-call durations from events recorded on the launch stream between consecutive calls (the queue stays
-        full; no synchronisation inside the series)."""
-        for _ in range(warm):
-            fn()
-        evs = [torch.cuda.Event(enable_timing=True) for _ in range(runs + 1)]
-        sync()
-        evs[0].record()
-        for i in range(runs):
-            fn()
-            evs[i + 1].record()
-        sync()
-        return np.array([evs[i].elapsed_time(evs[i + 1]) * 1e3 for i in range(runs)])
-
-    def percentiles(x):
-        return {"median_us": float(np.median(x)), "p10_us": float(np.percentile(x, 10)), "p90_us": float(np.percentile(x, 90)),
-                "mean_us": float(np.mean(x)), "runs": int(len(x))}
-
-    # the paper's timing protocol (Experiments, setup: 50 warm-up runs, 200 measured runs), per-step event times
-    extra["iteration_us_50warmup_200runs"] = percentiles(event_times_us(step, 50, 200))
+    extra["iteration_us_50warmup_200runs"] = protocol_run
 
     if not args.no_extras:
         # per-stage breakdown of one iteration (all stages carry events: slightly slower than t_iter)
