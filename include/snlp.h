@@ -101,7 +101,11 @@ int snlp_set_hc(snlp_ctx* ctx, const float* Hres, const float* pre, const float*
  * The library keeps data derived from the bound trace between calls (for large batches the correction leaves the
  * normalised branch inputs of the next round in the workspace; with snlp_set_skip_converged the count of exact layers).
  * A caller who writes into the bound trace itself must therefore bind it again (or call snlp_init_trace(_ex)) before
- * the next call that reads it. */
+ * the next call that reads it.
+ * Under HIP graph capture the same state decides, at capture time, which kernels a round consists of: a round
+ * captured directly after snlp_bind_trace or snlp_init_trace(_ex) recomputes every branch input and may be replayed
+ * after anything; a round captured after another round may be replayed only where such a round preceded it (capture
+ * the initialisation together with the rounds, or capture the first round after an initialisation). */
 int snlp_bind_trace(snlp_ctx* ctx, float* trace);
 
 /* Alg. 2 up to the solver loop.  snlp_set_prefix: the first S layers (0 <= S < L, default 0) are evaluated

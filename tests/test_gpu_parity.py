@@ -278,6 +278,55 @@ def test_bf16_path_small_shapes(gh, name, P, T, B, n, L):
     check_iterates(gh, shp, t, mode, [1, 2, L], TOL_BF16)
 
 
+@pytest.mark.parametrize("name,P,T,B,n,L", [
+    ("graph_decode_T8_P600", 600, 8, 2, 1, 3),      # decode attention with its own rotation, skinny GEMMs, two-kernel scan
+    ("graph_block_hcn_T40", 0, 40, 2, 4, 3),        # block attention, 128 x 128 GEMM tiles, 4 streams
+    # M d > 2^20: the eager rounds after the first take their branch inputs from the previous correction, the
+    # replayed round (captured after the initialisation) recomputes them -- the two must agree bit for bit
+    ("graph_prefill_T2060", 0, 2060, 2, 1, 2),
+])
+def test_rounds_replayed_from_a_hip_graph_equal_eager_rounds(gh, name, P, T, B, n, L):
+    """One round (evaluate + correct + probe) captured in a HIP graph and replayed L times, with eager work and
+    synchronisations of the same context between the replays, gives the eager trace and probe bit for bit after every
+    replay: the round enqueues kernels only (no allocation, no memset node), and a round captured directly after an
+    initialisation recomputes every branch input, so it does not depend on what ran between the replays."""
+    shp = si.Shape(name, L=L, d=256, n_heads=2, head_dim=128, d_mlp=512, B=B, T=T, P=P, n_streams=n, bf16=True, seed=77 + T)
+    t = si.generate(shp)
+    mode = oc.HCN if n > 1 else oc.IDN
+    m = gh.gpu_model(shp, t)
+    eager_tr, eager_pr = [], []
+    m.init_trace(m.h0)
+    for _ in range(L):
+        pr = torch.zeros((1, 2, L), dtype=torch.float32, device=m.trace.device)
+        m.iterate(mode, 1, pr)
+        torch.cuda.synchronize()
+        eager_tr.append(m.trace.clone()); eager_pr.append(pr.clone())
+    probe = torch.zeros((1, 2, L), dtype=torch.float32, device=m.trace.device)
+    cap = torch.cuda.Stream(device=m.trace.device)
+    cap.wait_stream(torch.cuda.current_stream(m.trace.device))
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(cap):
+        m.init_trace(m.h0)
+        m.iterate(mode, 1, probe)                 # warm-up on the capture stream
+        cap.synchronize()
+        m.init_trace(m.h0)
+        cap.synchronize()
+        with torch.cuda.graph(g, stream=cap):
+            m.iterate(mode, 1, probe)
+    torch.cuda.synchronize()
+    scratch = torch.empty_like(m.trace)
+    for k in range(L):
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(m.trace, eager_tr[k]), "%s: trace after replay %d differs from eager round %d" % (name, k + 1, k + 1)
+        assert torch.equal(probe, eager_pr[k]), "%s: probe after replay %d differs" % (name, k + 1)
+        # eager work of the same context between replays (its own output buffer; the bound trace is left alone)
+        m.sequential_forward(mode, m.h0, scratch)
+        torch.cuda.synchronize()
+    assert torch.equal(scratch, eager_tr[L - 1])     # K = L rounds equal the sequential trace, and both paths still agree
+    m.close()
+
+
 def test_bf16_gpu_invariants_and_hcn_identity(gh):
     """K = L recovers the GPU sequential trace bit for bit (batch-invariant kernels); HCN with H = I equals
     IDN bit for bit on the same model."""
