@@ -100,7 +100,7 @@ int snlp_set_hc(snlp_ctx* ctx, const float* Hres, const float* pre, const float*
 /* The trace [L+1, M, n, d] fp32; slot 0 is h_0 and is never written by snlp_iterate.
  * The library keeps data derived from the bound trace between calls (for large batches the correction leaves the
  * normalised branch inputs of the next round in the workspace; with snlp_set_skip_converged the count of exact layers).
- * A caller who writes into the bound trace itself must therefore bind it again (or call snlp_init_trace(_ex)) before
+ * A caller who writes into the bound trace must therefore bind it again (or call snlp_init_trace(_ex)) before
  * the next call that reads it.
  * Under HIP graph capture the same state decides, at capture time, which kernels a round consists of: a round
  * captured directly after snlp_bind_trace or snlp_init_trace(_ex) recomputes every branch input and may be replayed
