@@ -43,8 +43,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--skip-d26", action="store_true",
                     help="leave the d26 long-prefill workload out of the extras (1.7 GB of weights to generate)")
-    ap.add_argument("--prefill-only", action="store_true",
-                    help="run only the d20 HCN prefill section (M = 2048) and print its figures: for profiling the MFMA GEMMs")
+    ap.add_argument("--prefill-only", nargs="?", type=int, const=4, default=None, choices=(2, 4, 5), metavar="WORKLOAD",
+                    help="run only one prefill section and print its figures, for profiling its kernels: 4 = d20 HCN "
+                         "(M = 2048; the default), 2 = d12, 5 = d26 long prefill (T = 4096)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -117,8 +118,9 @@ def main():
         torch.cuda.empty_cache()
         return res
 
-    if args.prefill_only:
-        print(json.dumps({"d20_hcn_prefill": prefill_section(4)}), flush=True)
+    if args.prefill_only is not None:
+        key = {4: "d20_hcn_prefill", 2: "d12_prefill", 5: "d26_long_prefill"}[args.prefill_only]
+        print(json.dumps({key: prefill_section(args.prefill_only)}), flush=True)
         return
 
     shp = si.config(3, T=args.block)
