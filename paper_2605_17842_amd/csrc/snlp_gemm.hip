@@ -3,7 +3,8 @@
 //   C[l] = epilogue(A[l] (M x K) * W[l] (K x N)),  l = 0..Lc-1, one launch for all layers.
 // bf16 path: MFMA v_mfma_f32_32x32x16_bf16 with fp32 accumulation.  Three kernels:
 //   k_gemm_bf16_256  M > 128, launches with many tiles: 256 x 256 (or 256 x 128) x 64 tiles, both operands through a
-//                    five-unit LDS ring filled by direct-to-LDS loads; weights repacked [N, K];
+//                    five-unit LDS ring filled by direct-to-LDS loads; weights repacked [N, K]; the last incomplete
+//                    round of a launch may be cut into 256 x 128 or 256 x 64 pieces;
 //   k_gemm_bf16      M > 128, small launches: 128 x 128 tiles staged through padded LDS from registers;
 //   k_gemm_skinny    M <= 128: weights streamed from HBM straight into operand registers (repacked into MFMA operand
 //                    order), only the token tile through LDS.
@@ -155,10 +156,7 @@ struct TileCoord { int layer, tm, tn; };
 // own L2; consecutive logical tiles are therefore given to the SAME XCD, and within a layer tiles are
 // ordered in groups of 8 row-tiles x all column-tiles (column-major inside a group) so that the
 // tiles resident on an XCD at one time share A row-slabs and weight column-slabs.
-__device__ __forceinline__ TileCoord map_tile(unsigned pid, unsigned total, int tiles_m, int tiles_n) {
-  const unsigned q = total / 8, r = total % 8;
-  const unsigned xcd = pid % 8, local = pid / 8;
-  const unsigned t = xcd * q + (xcd < r ? xcd : r) + local;
+__device__ __forceinline__ TileCoord decode_tile(unsigned t, int tiles_m, int tiles_n) {
   const unsigned per_layer = (unsigned)tiles_m * tiles_n;
   TileCoord c;
   c.layer = (int)(t / per_layer);
@@ -171,6 +169,34 @@ __device__ __forceinline__ TileCoord map_tile(unsigned pid, unsigned total, int 
   c.tm = (int)(first_m + in % gsz);
   c.tn = (int)(in / gsz);
   return c;
+}
+
+__device__ __forceinline__ TileCoord map_tile(unsigned pid, unsigned total, int tiles_m, int tiles_n) {
+  const unsigned q = total / 8, r = total % 8;
+  const unsigned xcd = pid % 8, local = pid / 8;
+  return decode_tile(xcd * q + (xcd < r ? xcd : r) + local, tiles_m, tiles_n);
+}
+
+// The last, incomplete round of a launch of 256 x 256 tiles ("big tiles", index t in the order above) is cut into
+// narrower pieces: TileRange names big tiles [first, first + count), each cut into `parts` pieces of 256 x (256 /
+// parts) columns, the pieces of one big tile on one XCD.  A round of r < 256 big tiles takes as long as a full one;
+// as 2 r halves it takes three quarters of that, as 4 r quarters five eighths (a narrower tile moves more bytes per
+// flop), as long as the pieces fit one round.  Every piece runs the same k-ordered MFMA sequence per output element,
+// so nothing changes in the results.
+struct TileRange { unsigned first, count; int big_m, big_n, parts; };
+
+// Piece of tail workgroup `pid` (counted from the first tail workgroup), in units of 256 x BN tiles; false: the piece
+// lies outside the matrix or past the range.
+template <int BN>
+__device__ __forceinline__ bool map_tail_tile(unsigned pid, const TileRange& tr, int N, TileCoord& c) {
+  constexpr unsigned parts = 256 / BN;
+  const unsigned local = (pid / (8 * parts)) * 8 + pid % 8, part = (pid / 8) % parts;
+  if (local >= tr.count) return false;
+  const TileCoord b = decode_tile(tr.first + local, tr.big_m, tr.big_n);
+  c.layer = b.layer;
+  c.tm = b.tm;
+  c.tn = b.tn * (int)parts + (int)part;
+  return c.tn * BN < N;
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, bool C_BF16>
@@ -293,22 +319,19 @@ __global__ __launch_bounds__(kThreads) void k_gemm_bf16(const bf16_t* __restrict
   __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gptr),                   \
                                    (__attribute__((address_space(3))) void*)(lptr), 16, 0, 0)
 
-// BN = 256 or 128 output columns per workgroup (wave tile 64 x BN/2).  With 128 a weight unit fills half a slot
-// and the tile moves 1.5x the bytes per flop, but a launch too small for several rounds of 256 x 256 tiles (one
-// layer of the sequential path, narrow outputs) gets twice the workgroups.
+// One tile of 256 rows x BN columns, BN = 256, 128 or 64 (wave tile 64 x BN/2).  With 128 a weight unit fills half
+// a slot and the tile moves 1.5x the bytes per flop (with 64: 2.5x), but a launch too small for several rounds of
+// 256 x 256 tiles (one layer of the sequential path, narrow outputs) gets twice the workgroups, and the last
+// incomplete round of a big launch is cut into such tiles (see TileRange).
 template <int BN, int EPI, bool C_BF16>
-__global__ __launch_bounds__(512) void k_gemm_bf16_256(const bf16_t* __restrict__ A, size_t sA,
-                                                        const bf16_t* __restrict__ Wt, size_t sW, void* Cv, size_t sC,
-                                                        const float* __restrict__ R, size_t sR, int M, int N, int K,
-                                                        int tiles_m, int tiles_n, unsigned total_tiles, int a_group) {
-  static_assert(BN == 256 || BN == 128, "two column-tile widths");
+__device__ __forceinline__ void ring_tile(const TileCoord tc, bf16_t* __restrict__ ring, const bf16_t* __restrict__ A, size_t sA,
+                                          const bf16_t* __restrict__ Wt, size_t sW, void* Cv, size_t sC,
+                                          const float* __restrict__ R, size_t sR, int M, int N, int K, int a_group) {
+  static_assert(BN == 256 || BN == 128 || BN == 64, "three column-tile widths");
   constexpr int BM = 256;
   constexpr int TNF = BN / 64;       // 32-column MFMA tiles per wave
   constexpr int GW = BN / 64;        // 1 KB row groups of a weight unit per wave
   constexpr int kUnit = 256 * kBK;   // elements in a slot: 256 rows of 64 bf16 (a weight unit uses the first BN rows)
-  __shared__ __attribute__((aligned(16))) bf16_t ring[5 * kUnit];
-
-  const TileCoord tc = map_tile(blockIdx.x, total_tiles, tiles_m, tiles_n);
   A += (size_t)(tc.layer / a_group) * sA;
   Wt += (size_t)tc.layer * sW;
   const int m0 = tc.tm * BM, n0 = tc.tn * BN;
@@ -380,7 +403,7 @@ __global__ __launch_bounds__(512) void k_gemm_bf16_256(const bf16_t* __restrict_
       const bool loads = 2 * ks < kLoads;
       if (loads) {
 #pragma unroll
-        for (int u = 2 * ks; u < 2 * ks + 2; ++u) {
+        for (int u = 2 * ks; u < 2 * ks + 2 && u < kLoads; ++u) {
           if (u < GW) SNLP_GLDS16(ktw >= 0 ? gsrcW[u] + (size_t)ktw * kBK : Wt, dw + u * 512);
           else SNLP_GLDS16(kta >= 0 ? gsrcA[u - GW] + (size_t)kta * kBK : A, da + (u - GW) * 512);
         }
@@ -448,15 +471,44 @@ __global__ __launch_bounds__(512) void k_gemm_bf16_256(const bf16_t* __restrict_
   }
 }
 
-template <int BN>
+// Workgroups [0, head_tiles) take 256 x BN tiles in the launch's own order; with BNT != 0 the workgroups from
+// head_tiles on take the 256 x BNT pieces of the big tiles in `tail` (the last, incomplete round of a launch of
+// 256 x 256 tiles: in the same launch, so they start on the compute units the big tiles leave, with no kernel boundary
+// in between).
+template <int BN, int BNT, int EPI, bool C_BF16>
+__global__ __launch_bounds__(512) void k_gemm_bf16_256(const bf16_t* __restrict__ A, size_t sA,
+                                                        const bf16_t* __restrict__ Wt, size_t sW, void* Cv, size_t sC,
+                                                        const float* __restrict__ R, size_t sR, int M, int N, int K,
+                                                        int tiles_m, int tiles_n, unsigned head_tiles, int a_group,
+                                                        TileRange tail) {
+  __shared__ __attribute__((aligned(16))) bf16_t ring[5 * 256 * kBK];
+  TileCoord tc;
+  if (blockIdx.x < head_tiles) {                  // uniform over the workgroup
+    tc = map_tile(blockIdx.x, head_tiles, tiles_m, tiles_n);
+    ring_tile<BN, EPI, C_BF16>(tc, ring, A, sA, Wt, sW, Cv, sC, R, sR, M, N, K, a_group);
+    return;
+  }
+  if (BNT != 0) {
+    if (!map_tail_tile<(BNT != 0 ? BNT : 256)>(blockIdx.x - head_tiles, tail, N, tc)) return;   // whole workgroup
+    ring_tile<(BNT != 0 ? BNT : 256), EPI, C_BF16>(tc, ring, A, sA, Wt, sW, Cv, sC, R, sR, M, N, K, a_group);
+  }
+}
+
+constexpr TileRange kWholeGemm = {0u, 0u, 0, 0, 0};
+
+// BNT = 0: the whole GEMM in 256 x BN tiles.  BNT = 128 or 64 (BN = 256): big tiles [0, tail.first) whole, then the
+// pieces of `tail`.
+template <int BN, int BNT = 0>
 hipError_t launch_ring(hipStream_t s, int Lc, int M, int N, int K, const bf16_t* A, size_t sA, const bf16_t* Wt, size_t sW,
-                       void* C, size_t sC, bool c_bf16, int epi, const float* R, size_t sR, int a_group) {
+                       void* C, size_t sC, bool c_bf16, int epi, const float* R, size_t sR, int a_group,
+                       TileRange tail = kWholeGemm) {
   const int tiles_m = (M + 255) / 256, tiles_n = (N + BN - 1) / BN;
-  const unsigned total = (unsigned)Lc * tiles_m * tiles_n;
+  const unsigned head = BNT ? tail.first : (unsigned)Lc * tiles_m * tiles_n;
+  const unsigned total = head + (BNT ? (tail.count + 7) / 8 * 8 * (unsigned)tail.parts : 0u);
   dim3 grid(total), block(512);
 #define SNLP_GEMM256_LAUNCH(EPI_, CB_)                                                                               \
-  hipLaunchKernelGGL((k_gemm_bf16_256<BN, EPI_, CB_>), grid, block, 0, s, A, sA, Wt, sW, C, sC, R, sR, M, N, K, tiles_m, \
-                     tiles_n, total, a_group)
+  hipLaunchKernelGGL((k_gemm_bf16_256<BN, BNT, EPI_, CB_>), grid, block, 0, s, A, sA, Wt, sW, C, sC, R, sR, M, N, K, tiles_m, \
+                     tiles_n, head, a_group, tail)
   if (epi == EPI_STORE && c_bf16) SNLP_GEMM256_LAUNCH(EPI_STORE, true);
   else if (epi == EPI_STORE) SNLP_GEMM256_LAUNCH(EPI_STORE, false);
   else if (epi == EPI_RELU2 && c_bf16) SNLP_GEMM256_LAUNCH(EPI_RELU2, true);
@@ -827,7 +879,23 @@ hipError_t launch_gemm_bf16(hipStream_t s, int Lc, int M, int N, int K, const bf
   // workgroup per CU) needs about three rounds of workgroups behind its ramp and tail; with fp32 output and a
   // short k loop its unoverlapped epilogue costs more than the 128 x 128 kernel's extra LDS traffic unless
   // there are many rounds.  (Measured on the d12, d20 and d26 prefill shapes.)
-  const long tiles256 = (long)Lc * ((M + 255) / 256) * ((N + 255) / 256);
+  const int big_m = (M + 255) / 256, big_n = (N + 255) / 256;
+  const long tiles256 = (long)Lc * big_m * big_n;
+  // Whole rounds of 256 x 256 tiles with the last, incomplete round cut narrower in the same launch (see TileRange),
+  // where that is worth about 2 % of the launch or more: quarters (r <= 64) save 3/8 of a round, halves (r <= 128)
+  // 1/4.  Measured: d20 HCN PROJ (800 tiles, r = 32) 588 -> 522 us, O 171 -> 158, QKV (r = 96) 411 -> 405; d12 PROJ
+  // (288 tiles, before: 576 tiles of 256 x 128) 184 -> 147; d26 PROJ (r = 96 of 2912) 2292 -> 2217; launches of 33 and
+  // 43 rounds (d26 QKV, FC) gained nothing and keep the plain form.
+  if (K >= 128 && M >= 512 && N >= 512 && tiles256 >= 256 && (c_bf16 || K >= 1024 || tiles256 >= 2048)) {
+    const unsigned r = (unsigned)(tiles256 % 256), head = (unsigned)(tiles256 - r);
+    const long rounds = (tiles256 + 255) / 256;
+    if (r > 0 && r <= 64 && rounds <= 16)
+      return launch_ring<256, 64>(s, Lc, M, N, K, A, sA, W, sW, C, sC, c_bf16, epi, R, sR, a_group,
+                                  TileRange{head, r, big_m, big_n, 4});
+    if (r > 0 && r <= 128 && rounds <= 12)
+      return launch_ring<256, 128>(s, Lc, M, N, K, A, sA, W, sW, C, sC, c_bf16, epi, R, sR, a_group,
+                                   TileRange{head, r, big_m, big_n, 2});
+  }
   if (K >= 128 && M >= 512 && N >= 512 && tiles256 >= 768 && (c_bf16 || K >= 1024 || tiles256 >= 2048))
     return launch_ring<256>(s, Lc, M, N, K, A, sA, W, sW, C, sC, c_bf16, epi, R, sR, a_group);
   // Too few 256 x 256 tiles: 256 x 128 tiles of the same kernel when they give the CUs about one round or more
