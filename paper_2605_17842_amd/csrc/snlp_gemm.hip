@@ -884,9 +884,9 @@ hipError_t launch_gemm_bf16(hipStream_t s, int Lc, int M, int N, int K, const bf
   // Whole rounds of 256 x 256 tiles with the last, incomplete round cut narrower in the same launch (see TileRange),
   // where that is worth about 2 % of the launch or more: quarters (r <= 64) save 3/8 of a round, halves (r <= 128)
   // 1/4.  Measured: d20 HCN PROJ (800 tiles, r = 32) 588 -> 522 us, O 171 -> 158, QKV (r = 96) 411 -> 405; d12 PROJ
-  // (288 tiles, before: 576 tiles of 256 x 128) 184 -> 147; d26 PROJ (r = 96 of 2912) 2292 -> 2217; launches of 33 and
+  // (288 tiles, before: 576 tiles of 256 x 128) 184 -> 147, O (before: 128 x 128 tiles) 55 -> 52; d26 PROJ (r = 96 of 2912) 2292 -> 2217; launches of 33 and
   // 43 rounds (d26 QKV, FC) gained nothing and keep the plain form.
-  if (K >= 128 && M >= 512 && N >= 512 && tiles256 >= 256 && (c_bf16 || K >= 1024 || tiles256 >= 2048)) {
+  if (K >= 128 && M >= 512 && N >= 512 && tiles256 >= 256) {
     const unsigned r = (unsigned)(tiles256 % 256), head = (unsigned)(tiles256 - r);
     const long rounds = (tiles256 + 255) / 256;
     if (r > 0 && r <= 64 && rounds <= 16)
