@@ -485,6 +485,13 @@ __global__ __launch_bounds__(512) void k_gemm_bf16_256(const bf16_t* __restrict_
   TileCoord tc;
   if (blockIdx.x < head_tiles) {                  // uniform over the workgroup
     tc = map_tile(blockIdx.x, head_tiles, tiles_m, tiles_n);
+    if (BN == 256 && BNT == 128 && tc.tn * 256 + 128 >= N) {
+      // the last column tile of a matrix whose width is an odd multiple of 128 is half empty: it runs as a half
+      // (where the launch carries that body anyway)
+      tc.tn *= 2;
+      ring_tile<(BNT == 128 ? 128 : BN), EPI, C_BF16>(tc, ring, A, sA, Wt, sW, Cv, sC, R, sR, M, N, K, a_group);
+      return;
+    }
     ring_tile<BN, EPI, C_BF16>(tc, ring, A, sA, Wt, sW, Cv, sC, R, sR, M, N, K, a_group);
     return;
   }
