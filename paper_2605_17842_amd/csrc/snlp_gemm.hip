@@ -178,25 +178,26 @@ __device__ __forceinline__ TileCoord map_tile(unsigned pid, unsigned total, int 
 }
 
 // The last, incomplete round of a launch of 256 x 256 tiles ("big tiles", index t in the order above) is cut into
-// narrower pieces: TileRange names big tiles [first, first + count), each cut into `parts` pieces of 256 x (256 /
-// parts) columns, the pieces of one big tile on one XCD.  A round of r < 256 big tiles takes as long as a full one;
-// as 2 r halves it takes three quarters of that, as 4 r quarters five eighths (a narrower tile moves more bytes per
-// flop), as long as the pieces fit one round.  Every piece runs the same k-ordered MFMA sequence per output element,
-// so nothing changes in the results.
+// smaller pieces: TileRange names big tiles [first, first + count), each cut into `parts` pieces of BM x BN outputs
+// (256 x 128: 2, 128 x 128: 4, 128 x 64: 8), the pieces of one big tile on one XCD.  A round of r < 256 big tiles takes
+// as long as a full one; a piece's time goes with the operand bytes it moves, (BM + BN) / 512 of a big tile's at best,
+// so as 2 r halves the round takes three quarters of that, as 4 r pieces of 128 x 128 one half, as 8 r pieces of
+// 128 x 64 three eighths (measured: 0.47) -- as long as the pieces fit one round.  Every piece runs the same k-ordered
+// MFMA sequence per output element, so nothing changes in the results.
 struct TileRange { unsigned first, count; int big_m, big_n, parts; };
 
-// Piece of tail workgroup `pid` (counted from the first tail workgroup), in units of 256 x BN tiles; false: the piece
+// Piece of tail workgroup `pid` (counted from the first tail workgroup), in units of BM x BN tiles; false: the piece
 // lies outside the matrix or past the range.
-template <int BN>
-__device__ __forceinline__ bool map_tail_tile(unsigned pid, const TileRange& tr, int N, TileCoord& c) {
-  constexpr unsigned parts = 256 / BN;
+template <int BM, int BN>
+__device__ __forceinline__ bool map_tail_tile(unsigned pid, const TileRange& tr, int M, int N, TileCoord& c) {
+  constexpr unsigned parts_n = 256 / BN, parts = (256 / BM) * parts_n;
   const unsigned local = (pid / (8 * parts)) * 8 + pid % 8, part = (pid / 8) % parts;
   if (local >= tr.count) return false;
   const TileCoord b = decode_tile(tr.first + local, tr.big_m, tr.big_n);
   c.layer = b.layer;
-  c.tm = b.tm;
-  c.tn = b.tn * (int)parts + (int)part;
-  return c.tn * BN < N;
+  c.tm = b.tm * (256 / BM) + (int)(part / parts_n);
+  c.tn = b.tn * (int)parts_n + (int)(part % parts_n);
+  return c.tm * BM < M && c.tn * BN < N;
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, bool C_BF16>
@@ -319,15 +320,15 @@ __global__ __launch_bounds__(kThreads) void k_gemm_bf16(const bf16_t* __restrict
   __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gptr),                   \
                                    (__attribute__((address_space(3))) void*)(lptr), 16, 0, 0)
 
-// One tile of 256 rows x BN columns, BN = 256, 128 or 64 (wave tile 64 x BN/2).  With 128 a weight unit fills half
-// a slot and the tile moves 1.5x the bytes per flop (with 64: 2.5x), but a launch too small for several rounds of
-// 256 x 256 tiles (one layer of the sequential path, narrow outputs) gets twice the workgroups, and the last
-// incomplete round of a big launch is cut into such tiles (see TileRange).
+// One tile of 256 rows x BN columns, BN = 256 or 128 (wave tile 64 x BN/2).  With 128 a weight unit fills half a
+// slot and the tile moves 1.5x the bytes per flop, but a launch too small for several rounds of 256 x 256 tiles (one
+// layer of the sequential path, narrow outputs) gets twice the workgroups, and the last incomplete round of a big
+// launch may be cut into such tiles (see TileRange).
 template <int BN, int EPI, bool C_BF16>
 __device__ __forceinline__ void ring_tile(const TileCoord tc, bf16_t* __restrict__ ring, const bf16_t* __restrict__ A, size_t sA,
                                           const bf16_t* __restrict__ Wt, size_t sW, void* Cv, size_t sC,
                                           const float* __restrict__ R, size_t sR, int M, int N, int K, int a_group) {
-  static_assert(BN == 256 || BN == 128 || BN == 64, "three column-tile widths");
+  static_assert(BN == 256 || BN == 128, "two column-tile widths");
   constexpr int BM = 256;
   constexpr int TNF = BN / 64;       // 32-column MFMA tiles per wave
   constexpr int GW = BN / 64;        // 1 KB row groups of a weight unit per wave
@@ -471,11 +472,118 @@ __device__ __forceinline__ void ring_tile(const TileCoord tc, bf16_t* __restrict
   }
 }
 
+// The same load written out (m0 = LDS base of the wave's 1 KB, lane i's 16 bytes land at base + 16 i): the compiler does
+// not know of it, so it adds no waits of its own and the counted s_waitcnt of the loop below is the only one.  (Behind
+// the builtin it makes LDS reads wait for every outstanding load whose ring slot it cannot tell from theirs.)
+#define SNLP_GLDS16_ASM(gptr, lptr)                                                                          \
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"                               \
+               :: "v"(gptr), "s"((uint32_t)(size_t)((__attribute__((address_space(3))) char*)(lptr)))        \
+               : "memory", "m0")
+
+// A piece of 128 x BN outputs (BN = 128 or 64) of the last, incomplete round of a launch (see TileRange): 8 waves as
+// 4 x 2, wave tile 32 x BN/2, same k-ordered MFMA sequence per output element as every other tile shape.  A piece
+// moves few bytes per k-tile (32 or 24 KB), so what bounds it is not the fill rate but how far ahead its operands are
+// requested: in the five-unit ring above the weight unit of k-tile kt + 1 is requested during k-tile kt, and a
+// k-tile cannot take less than that load's latency (about 1.1 us under load, which is what 256 x 64 and 128 x 64
+// pieces both took per k-tile there; with the deeper ring a 128 x 64 piece takes 0.8 us).  Here the 160 KB hold D = 5 (128 x 128) or 6 (128 x 64) whole k-tiles, A rows
+// then weight rows, and k-tile kt + D - 1 is requested while kt is multiplied.
+template <int BM, int BN, int EPI, bool C_BF16>
+__device__ __forceinline__ void ring_piece(const TileCoord tc, bf16_t* __restrict__ ring, const bf16_t* __restrict__ A, size_t sA,
+                                           const bf16_t* __restrict__ Wt, size_t sW, void* Cv, size_t sC,
+                                           const float* __restrict__ R, size_t sR, int M, int N, int K, int a_group) {
+  static_assert(BM == 128 && (BN == 128 || BN == 64), "two piece shapes");
+  constexpr int TNF = BN / 64;                    // 32-column MFMA tiles per wave
+  constexpr int GA = BM / 64, GW = BN / 64;       // 1 KB row groups (8 rows) per wave of a k-tile's A and weight rows
+  constexpr int kStage = (BM + BN) * kBK;         // elements of one k-tile in the ring
+  constexpr int D = (5 * 256 * kBK) / kStage;     // k-tiles the ring holds
+  A += (size_t)(tc.layer / a_group) * sA;
+  Wt += (size_t)tc.layer * sW;
+  const int m0 = tc.tm * BM, n0 = tc.tn * BN;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+
+  const bf16_t* gsrcA[GA];
+  const bf16_t* gsrcW[GW];
+#pragma unroll
+  for (int j = 0; j < GA; ++j) {
+    const int row = (wave * GA + j) * 8 + (lane >> 3);
+    const int chunk = (lane & 7) ^ ((row >> 1) & 7);
+    int ra = m0 + row;
+    ra = ra < M ? ra : M - 1;
+    gsrcA[j] = A + (size_t)ra * K + chunk * 8;
+  }
+#pragma unroll
+  for (int j = 0; j < GW; ++j) {
+    const int row = (wave * GW + j) * 8 + (lane >> 3);
+    const int chunk = (lane & 7) ^ ((row >> 1) & 7);
+    int rw = n0 + row;
+    rw = rw < N ? rw : N - 1;
+    gsrcW[j] = Wt + (size_t)rw * K + chunk * 8;
+  }
+  const int nk = K / kBK;
+  // Past the end of K every lane requests the operand's first 16 bytes instead (one sector, into a stage nobody reads
+  // again), which keeps the number of loads per phase, and with it the wait count, the same in every phase.
+  auto issue = [&](int kt, int stage) {
+    bf16_t* da = ring + stage * kStage + wave * GA * 512;
+    bf16_t* dw = ring + stage * kStage + BM * kBK + wave * GW * 512;
+    const bool real = kt < nk;
+#pragma unroll
+    for (int j = 0; j < GA; ++j) SNLP_GLDS16_ASM(real ? gsrcA[j] + (size_t)kt * kBK : A, da + j * 512);
+#pragma unroll
+    for (int j = 0; j < GW; ++j) SNLP_GLDS16_ASM(real ? gsrcW[j] + (size_t)kt * kBK : Wt, dw + j * 512);
+  };
+
+  f32x16_t acc[TNF];
+#pragma unroll
+  for (int j = 0; j < TNF; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+
+  const int sw = ((lane & 31) >> 1) & 7, hi = lane >> 5;
+  const int rowoff = (lane & 31) * kBK;
+#pragma unroll
+  for (int t = 0; t < D - 1; ++t) issue(t, t);
+  int stage = 0;   // stage of k-tile kt; k-tile kt + D - 1 goes to the stage before it
+  for (int kt = 0; kt < nk; ++kt) {
+    // this wave's part of k-tile kt has landed (loads return in order; those of the D - 2 k-tiles after it may still
+    // be on their way); behind the barrier everyone's has, and everyone is done with k-tile kt - 1, whose stage the
+    // loads of this phase refill
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((D - 2) * (GA + GW)) : "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    issue(kt + D - 1, stage == 0 ? D - 1 : stage - 1);
+    const bf16_t* ua = ring + stage * kStage;
+    const bf16_t* uw = ua + BM * kBK;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const int off = rowoff + (((ks * 2 + hi) ^ sw) << 3);
+      const bf16x8_t af = *reinterpret_cast<const bf16x8_t*>(ua + wm * 32 * kBK + off);
+#pragma unroll
+      for (int j = 0; j < TNF; ++j) {
+        const bf16x8_t bfr = *reinterpret_cast<const bf16x8_t*>(uw + (wn * (BN / 2) + j * 32) * kBK + off);
+        acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bfr, acc[j], 0, 0, 0);
+      }
+    }
+    stage = stage + 1 == D ? 0 : stage + 1;
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the filler loads have landed before the LDS is given back
+
+  const int col_in = lane & 31, row_in = (lane >> 5) * 4;
+#pragma unroll
+  for (int j = 0; j < TNF; ++j) {
+    const int col = n0 + wn * (BN / 2) + j * 32 + col_in;
+    if (col >= N) continue;
+    store_block<EPI, C_BF16>(acc[j], layer_ptr<C_BF16>(Cv, (size_t)tc.layer * sC), R ? R + (size_t)tc.layer * sR : nullptr,
+                             m0 + wm * 32, row_in, col, M, N);
+  }
+}
+
 // Workgroups [0, head_tiles) take 256 x BN tiles in the launch's own order; with BNT != 0 the workgroups from
-// head_tiles on take the 256 x BNT pieces of the big tiles in `tail` (the last, incomplete round of a launch of
+// head_tiles on take the BMT x BNT pieces of the big tiles in `tail` (the last, incomplete round of a launch of
 // 256 x 256 tiles: in the same launch, so they start on the compute units the big tiles leave, with no kernel boundary
 // in between).
-template <int BN, int BNT, int EPI, bool C_BF16>
+template <int BN, int BMT, int BNT, int EPI, bool C_BF16>
 __global__ __launch_bounds__(512) void k_gemm_bf16_256(const bf16_t* __restrict__ A, size_t sA,
                                                         const bf16_t* __restrict__ Wt, size_t sW, void* Cv, size_t sC,
                                                         const float* __restrict__ R, size_t sR, int M, int N, int K,
@@ -485,27 +593,29 @@ __global__ __launch_bounds__(512) void k_gemm_bf16_256(const bf16_t* __restrict_
   TileCoord tc;
   if (blockIdx.x < head_tiles) {                  // uniform over the workgroup
     tc = map_tile(blockIdx.x, head_tiles, tiles_m, tiles_n);
-    if (BN == 256 && BNT == 128 && tc.tn * 256 + 128 >= N) {
+    if (BN == 256 && BMT == 256 && BNT == 128 && tc.tn * 256 + 128 >= N) {
       // the last column tile of a matrix whose width is an odd multiple of 128 is half empty: it runs as a half
       // (where the launch carries that body anyway)
       tc.tn *= 2;
-      ring_tile<(BNT == 128 ? 128 : BN), EPI, C_BF16>(tc, ring, A, sA, Wt, sW, Cv, sC, R, sR, M, N, K, a_group);
+      ring_tile<(BMT == 256 && BNT == 128 ? 128 : BN), EPI, C_BF16>(tc, ring, A, sA, Wt, sW, Cv, sC, R, sR, M, N, K, a_group);
       return;
     }
     ring_tile<BN, EPI, C_BF16>(tc, ring, A, sA, Wt, sW, Cv, sC, R, sR, M, N, K, a_group);
     return;
   }
   if (BNT != 0) {
-    if (!map_tail_tile<(BNT != 0 ? BNT : 256)>(blockIdx.x - head_tiles, tail, N, tc)) return;   // whole workgroup
-    ring_tile<(BNT != 0 ? BNT : 256), EPI, C_BF16>(tc, ring, A, sA, Wt, sW, Cv, sC, R, sR, M, N, K, a_group);
+    constexpr int PM = BNT != 0 ? BMT : 256, PN = BNT != 0 ? BNT : 256;
+    if (!map_tail_tile<PM, PN>(blockIdx.x - head_tiles, tail, M, N, tc)) return;   // whole workgroup
+    if constexpr (PM == 128) ring_piece<PM, PN, EPI, C_BF16>(tc, ring, A, sA, Wt, sW, Cv, sC, R, sR, M, N, K, a_group);
+    else ring_tile<PN, EPI, C_BF16>(tc, ring, A, sA, Wt, sW, Cv, sC, R, sR, M, N, K, a_group);
   }
 }
 
 constexpr TileRange kWholeGemm = {0u, 0u, 0, 0, 0};
 
-// BNT = 0: the whole GEMM in 256 x BN tiles.  BNT = 128 or 64 (BN = 256): big tiles [0, tail.first) whole, then the
+// BNT = 0: the whole GEMM in 256 x BN tiles.  Else (BN = 256): big tiles [0, tail.first) whole, then the BMT x BNT
 // pieces of `tail`.
-template <int BN, int BNT = 0>
+template <int BN, int BMT = 256, int BNT = 0>
 hipError_t launch_ring(hipStream_t s, int Lc, int M, int N, int K, const bf16_t* A, size_t sA, const bf16_t* Wt, size_t sW,
                        void* C, size_t sC, bool c_bf16, int epi, const float* R, size_t sR, int a_group,
                        TileRange tail = kWholeGemm) {
@@ -514,7 +624,7 @@ hipError_t launch_ring(hipStream_t s, int Lc, int M, int N, int K, const bf16_t*
   const unsigned total = head + (BNT ? (tail.count + 7) / 8 * 8 * (unsigned)tail.parts : 0u);
   dim3 grid(total), block(512);
 #define SNLP_GEMM256_LAUNCH(EPI_, CB_)                                                                               \
-  hipLaunchKernelGGL((k_gemm_bf16_256<BN, BNT, EPI_, CB_>), grid, block, 0, s, A, sA, Wt, sW, C, sC, R, sR, M, N, K, tiles_m, \
+  hipLaunchKernelGGL((k_gemm_bf16_256<BN, BMT, BNT, EPI_, CB_>), grid, block, 0, s, A, sA, Wt, sW, C, sC, R, sR, M, N, K, tiles_m, \
                      tiles_n, head, a_group, tail)
   if (epi == EPI_STORE && c_bf16) SNLP_GEMM256_LAUNCH(EPI_STORE, true);
   else if (epi == EPI_STORE) SNLP_GEMM256_LAUNCH(EPI_STORE, false);
@@ -888,20 +998,24 @@ hipError_t launch_gemm_bf16(hipStream_t s, int Lc, int M, int N, int K, const bf
   // there are many rounds.  (Measured on the d12, d20 and d26 prefill shapes.)
   const int big_m = (M + 255) / 256, big_n = (N + 255) / 256;
   const long tiles256 = (long)Lc * big_m * big_n;
-  // Whole rounds of 256 x 256 tiles with the last, incomplete round cut narrower in the same launch (see TileRange),
-  // where that is worth about 2 % of the launch or more: quarters (r <= 64) save 3/8 of a round, halves (r <= 128)
-  // 1/4.  Measured: d20 HCN PROJ (800 tiles, r = 32) 588 -> 522 us, O 171 -> 158, QKV (r = 96) 411 -> 405; d12 PROJ
-  // (288 tiles, before: 576 tiles of 256 x 128) 184 -> 147, O (before: 128 x 128 tiles) 55 -> 52; d26 PROJ (r = 96 of 2912) 2292 -> 2217; launches of 33 and
-  // 43 rounds (d26 QKV, FC) gained nothing and keep the plain form.
+  // Whole rounds of 256 x 256 tiles with the last, incomplete round cut smaller in the same launch (see TileRange),
+  // where that is worth about 2 % of the launch or more: as 128 x 64 pieces (r <= 32) the round takes a little under
+  // half of a full one, as 128 x 128 pieces (r <= 64) a little over half, as halves (r <= 128) three quarters.
+  // Measured: d20 HCN PROJ (800 tiles, r = 32) 588 -> 490 us, O 171 -> 149, QKV (r = 96) 411 -> 405; d12 PROJ (288
+  // tiles, before: 576 tiles of 256 x 128) 184 -> 132, O (before: 128 x 128 tiles) 55 -> 48; d26 PROJ (r = 96 of 2912)
+  // 2292 -> 2217; launches of 33 and 43 rounds (d26 QKV, FC) gained nothing from halves and keep the plain form.
   if (K >= 128 && M >= 512 && N >= 512 && tiles256 >= 256) {
     const unsigned r = (unsigned)(tiles256 % 256), head = (unsigned)(tiles256 - r);
     const long rounds = (tiles256 + 255) / 256;
-    if (r > 0 && r <= 64 && rounds <= 16)
-      return launch_ring<256, 64>(s, Lc, M, N, K, A, sA, W, sW, C, sC, c_bf16, epi, R, sR, a_group,
-                                  TileRange{head, r, big_m, big_n, 4});
+    if (r > 0 && r <= 32 && rounds <= 24)
+      return launch_ring<256, 128, 64>(s, Lc, M, N, K, A, sA, W, sW, C, sC, c_bf16, epi, R, sR, a_group,
+                                       TileRange{head, r, big_m, big_n, 8});
+    if (r > 0 && r <= 64 && rounds <= 20)
+      return launch_ring<256, 128, 128>(s, Lc, M, N, K, A, sA, W, sW, C, sC, c_bf16, epi, R, sR, a_group,
+                                        TileRange{head, r, big_m, big_n, 4});
     if (r > 0 && r <= 128 && rounds <= 12)
-      return launch_ring<256, 128>(s, Lc, M, N, K, A, sA, W, sW, C, sC, c_bf16, epi, R, sR, a_group,
-                                   TileRange{head, r, big_m, big_n, 2});
+      return launch_ring<256, 256, 128>(s, Lc, M, N, K, A, sA, W, sW, C, sC, c_bf16, epi, R, sR, a_group,
+                                        TileRange{head, r, big_m, big_n, 2});
   }
   if (K >= 128 && M >= 512 && N >= 512 && tiles256 >= 768 && (c_bf16 || K >= 1024 || tiles256 >= 2048))
     return launch_ring<256>(s, Lc, M, N, K, A, sA, W, sW, C, sC, c_bf16, epi, R, sR, a_group);

@@ -111,6 +111,19 @@ def _edge(T, P, seed):
 EDGE_CASES = [_edge(T, P, 920 + i) for i, (T, P) in enumerate([
     (17, 0), (31, 1), (32, 32), (33, 31), (63, 64), (64, 33), (65, 95), (127, 0), (128, 64), (129, 63), (255, 1), (257, 160)])]
 
+# Deep, narrow prefill models whose layer-batched GEMM launches end in an incomplete round of 256 x 256 tiles, with
+# M = 600 rows (2.3 row tiles) and output widths of 2.5, 7.5 and 5.25 column tiles: d = 640, d_mlp = 1344, so O / PROJ
+# have 9 tiles per layer, QKV 24, FC 18.  30 layers: O / PROJ 270 tiles and FC 540, remainders 14 and 28 (cut into
+# 128 x 64 pieces; QKV 720, remainder 208, stays whole).  34 layers: O / PROJ 306 and QKV 816, remainders 50 and 48
+# (128 x 128 pieces), FC 612, remainder 100 (256 x 128 halves, and the half-empty last column tile runs as a half).
+# The remainder's tiles are the last in launch order, so the last two layers are compared, and the first.
+def _tail(name, L, seed):
+    shp = si.Shape(name, L=L, d=640, n_heads=5, head_dim=128, d_mlp=1344, B=3, T=200, P=0, n_streams=1, bf16=True, seed=seed)
+    return StageCase(name, shp, layers=(1, L - 1, L), second_state=False)
+
+
+TAIL_CASES = [_tail("gemm_tail_L30", 30, 940), _tail("gemm_tail_L34", 34, 941)]
+
 # The benchmark workloads at full size (GPU test only).
 FULL_CASES = [
     StageCase("d20_decode_T8", si.config(3, T=8)),

@@ -700,3 +700,24 @@ def test_decode_gemm_wide_column_tiles(gh, name, d, F, B):
     torch.cuda.synchronize()
     assert torch.equal(m.trace, seq)
     m.close()
+
+
+@pytest.mark.gpu
+def test_prefill_gemm_tail_pieces_equal_whole_tiles(gh):
+    """Prefill GEMM launches cut the last, incomplete round of 256 x 256 tiles into smaller pieces, by the launch
+    size.  On a deep, narrow model with ragged rows and columns (600 rows; widths of 2.5, 7.5 and 5.25 tiles), K = L
+    rounds that leave converged layers out run launches of 34, 33, ... 1 layers, whose remainders pass through every
+    piece shape and the plain form; the one-layer launches of the sequential path use other tile shapes again.  Every
+    output element is the same k-ordered sum in all of them, so the two traces must agree bit for bit (parity of the
+    pieces with the oracle: the stage test on the same shape)."""
+    shp = si.Shape("gemm_tail_L34", L=34, d=640, n_heads=5, head_dim=128, d_mlp=1344, B=3, T=200, P=0, seed=941)
+    t = si.generate(shp)
+    say("gemm_tail_L34 M=%d" % shp.M)
+    m = gh.gpu_model(shp, t)
+    seq = m.sequential_forward(0, m.h0).clone()
+    m.set_skip_converged(True)
+    m.init_trace(m.h0)
+    m.iterate(0, shp.L, None)
+    torch.cuda.synchronize()
+    assert torch.equal(m.trace, seq)
+    m.close()

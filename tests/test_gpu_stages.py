@@ -92,6 +92,12 @@ def test_stage_parity_block_kernel_edges(case):
     run_stage_case(case)
 
 
+@pytest.mark.parametrize("case", sc.TAIL_CASES, ids=lambda c: c.name)
+def test_stage_parity_gemm_tail_pieces(case):
+    """The pieces that the last, incomplete round of a prefill GEMM launch is cut into, on ragged rows and columns."""
+    run_stage_case(case)
+
+
 @pytest.mark.parametrize("case", sc.FULL_CASES, ids=lambda c: c.name)
 def test_stage_parity_d20_workloads(case):
     run_stage_case(case)
