@@ -1017,8 +1017,14 @@ hipError_t launch_gemm_bf16(hipStream_t s, int Lc, int M, int N, int K, const bf
       return launch_ring<256, 256, 128>(s, Lc, M, N, K, A, sA, W, sW, C, sC, c_bf16, epi, R, sR, a_group,
                                         TileRange{head, r, big_m, big_n, 2});
   }
-  if (K >= 128 && M >= 512 && N >= 512 && tiles256 >= 768 && (c_bf16 || K >= 1024 || tiles256 >= 2048))
+  if (K >= 128 && M >= 512 && N >= 512 && tiles256 >= 768 && (c_bf16 || K >= 1024 || tiles256 >= 2048)) {
+    // a width that ends in a half-empty column tile (d26 QKV: 19.5 tiles) takes the launch that carries the
+    // 256 x 128 body, with no tail pieces, so that those tiles run as halves
+    if (N % 256 != 0 && N % 256 <= 128)
+      return launch_ring<256, 256, 128>(s, Lc, M, N, K, A, sA, W, sW, C, sC, c_bf16, epi, R, sR, a_group,
+                                        TileRange{(unsigned)tiles256, 0u, big_m, big_n, 2});
     return launch_ring<256>(s, Lc, M, N, K, A, sA, W, sW, C, sC, c_bf16, epi, R, sR, a_group);
+  }
   // Too few 256 x 256 tiles: 256 x 128 tiles of the same kernel when they give the CUs about one round or more
   // (one layer of the sequential path at prefill sizes, narrow outputs; as above not for fp32 output behind a short
   // k loop), else 128 x 128 tiles.  Measured: one d20 layer's QKV 31 -> 27 us, d26 PROJ 116 -> 104, d12 batched PROJ
