@@ -839,11 +839,30 @@ __global__ __launch_bounds__(64 * NW, TN_HI == 1 ? 2 : 1) void k_gemm_skinny(con
   A += (size_t)(layer / a_group) * sA;
   Wp += (size_t)layer * sW;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  // The token tile of a layer is read k-tile by k-tile, 128 bytes of each of its rows at a time, by all the workgroups
+  // of the layer (one XCD, see above): whoever asks first brings the line in from DRAM, and under the saturated weight
+  // stream such single-line reads, each in a DRAM row of its own, come back late (the decode attention kernel shows the
+  // same with its block rows).  So before it starts streaming, every workgroup reads one word of each line of its share
+  // of the layer's token rows -- whole rows, at a moment when the memory system is idle -- and the k-tile loads then
+  // hit in L2.  d20 decode: QKV 48.9 -> 43.7 us, FC 62.3 -> 55.8, O 25.4 -> 24.3; PROJ unchanged (its token tile was
+  // written by the FC launch on the same XCD and is still in that L2).  The words are read and dropped.
+  unsigned touched = 0;
+  {
+    const int lines_per_row = K / 64;                          // 128-byte lines of a token row
+    const int rows = M - m0 < BM ? M - m0 : BM;
+    const int total = rows * lines_per_row;
+    const int lo = (int)((long)total * tn / tiles_n), hi = (int)((long)total * (tn + 1) / tiles_n);
+    for (int ln = lo + (int)threadIdx.x; ln < hi; ln += 64 * NW) {
+      const int r = ln / lines_per_row, c = ln % lines_per_row;
+      touched ^= *reinterpret_cast<const unsigned*>(A + (size_t)(m0 + r) * K + c * 64);
+    }
+  }
   if (NH == NW || wave < NH)
     skinny_wave<TM, TN_HI, NW, DEPTH, EPI, C_BF16>(A, Wp, Cv, sC, R, sR, M, N, K, layer, m0, tn * BLOCKS + wave * TN_HI, lds);
   else
     skinny_wave<TM, TN_LO, NW, DEPTH, EPI, C_BF16>(A, Wp, Cv, sC, R, sR, M, N, K, layer, m0,
                                                    tn * BLOCKS + NH * TN_HI + (wave - NH) * TN_LO, lds);
+  asm volatile("" :: "v"(touched));   // keeps the touching loads
 }
 
 // [L][K][N] row-major -> operand order [L][N/32][K/16][64][8]
