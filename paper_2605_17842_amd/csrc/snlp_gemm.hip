@@ -822,7 +822,7 @@ __global__ __launch_bounds__(64 * NW, TN_HI == 1 ? 2 : 1) void k_gemm_skinny(con
                                                                         const bf16_t* __restrict__ Wp, size_t sW, void* Cv,
                                                                         size_t sC, const float* __restrict__ R, size_t sR,
                                                                         int M, int N, int K, int tiles_m, int tiles_n,
-                                                                        unsigned total_tiles, int a_group) {
+                                                                        unsigned total_tiles, int a_group, int touch_a) {
   constexpr int BM = 32 * TM;
   constexpr int TILE = BM * kLdsRow;
   constexpr int BLOCKS = NH * TN_HI + (NW - NH) * TN_LO;   // column blocks per workgroup
@@ -845,9 +845,11 @@ __global__ __launch_bounds__(64 * NW, TN_HI == 1 ? 2 : 1) void k_gemm_skinny(con
   // same with its block rows).  So before it starts streaming, every workgroup reads one word of each line of its share
   // of the layer's token rows -- whole rows, at a moment when the memory system is idle -- and the k-tile loads then
   // hit in L2.  d20 decode: QKV 48.9 -> 43.7 us, FC 62.3 -> 55.8, O 25.4 -> 24.3; PROJ unchanged (its token tile was
-  // written by the FC launch on the same XCD and is still in that L2).  The words are read and dropped.
+  // written by the FC launch on the same XCD and is still in that L2).  The words are read and dropped.  Only in
+  // launches that stream enough weights to saturate the memory system (the launcher's flag): one layer alone loses
+  // half a microsecond to it.
   unsigned touched = 0;
-  {
+  if (touch_a) {
     const int lines_per_row = K / 64;                          // 128-byte lines of a token row
     const int rows = M - m0 < BM ? M - m0 : BM;
     const int total = rows * lines_per_row;
@@ -887,10 +889,11 @@ hipError_t launch_skinny(hipStream_t s, int Lc, int M, int N, int K, const bf16_
   constexpr int BLOCKS = NH * TN + (NW - NH) * TN_LO;   // 32-column blocks per workgroup
   const int tiles_n = (N + 32 * BLOCKS - 1) / (32 * BLOCKS), tiles_m = (M + 32 * TM - 1) / (32 * TM);
   const unsigned total = (unsigned)Lc * tiles_m * tiles_n;
+  const int touch_a = (size_t)Lc * N * K * sizeof(bf16_t) >= ((size_t)32 << 20) ? 1 : 0;   // see k_gemm_skinny
   dim3 grid(total), block(64 * NW);
 #define SNLP_SKINNY_LAUNCH(EPI_, CB_)                                                                           \
   hipLaunchKernelGGL((k_gemm_skinny<TM, TN, TN_LO, NH, NW, DEPTH, EPI_, CB_>), grid, block, 0, s, A, sA, Wp, sW, C, sC, R, sR, \
-                     M, N, K, tiles_m, tiles_n, total, a_group)
+                     M, N, K, tiles_m, tiles_n, total, a_group, touch_a)
   if (epi == EPI_STORE && c_bf16) SNLP_SKINNY_LAUNCH(EPI_STORE, true);
   else if (epi == EPI_STORE) SNLP_SKINNY_LAUNCH(EPI_STORE, false);
   else if (epi == EPI_RELU2 && c_bf16) SNLP_SKINNY_LAUNCH(EPI_RELU2, true);
