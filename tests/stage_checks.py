@@ -124,6 +124,18 @@ def _tail(name, L, seed):
 
 TAIL_CASES = [_tail("gemm_tail_L30", 30, 940), _tail("gemm_tail_L34", 34, 941)]
 
+# Decode launches of more than 512 (layer, sequence, head) items, where the workgroups of the first round also touch
+# the block rows of later ones: 576 and 1300 items (neither a multiple of 512), 5 and 16 block rows, prefixes that do
+# not end on a tile boundary (GPU test only; the layers whose items are touched, and the first, are compared).
+def _touch(name, L, B, T, P, seed, layers):
+    return StageCase(name, small(name, L=L, B=B, T=T, P=P, seed=seed), layers=layers, second_state=False)
+
+
+DECODE_MANY_ITEMS_CASES = [
+    _touch("decode_576_items_T5_P523", 24, 12, 5, 523, 950, (1, 22, 24)),
+    _touch("decode_1300_items_T16_P70", 50, 13, 16, 70, 951, (1, 21, 41, 50)),
+]
+
 # The benchmark workloads at full size (GPU test only).
 FULL_CASES = [
     StageCase("d20_decode_T8", si.config(3, T=8)),

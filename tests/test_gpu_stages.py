@@ -92,6 +92,12 @@ def test_stage_parity_block_kernel_edges(case):
     run_stage_case(case)
 
 
+@pytest.mark.parametrize("case", sc.DECODE_MANY_ITEMS_CASES, ids=lambda c: c.name)
+def test_stage_parity_decode_launches_of_many_items(case):
+    """Decode attention launches longer than one round of workgroups (the first round reads ahead for the later ones)."""
+    run_stage_case(case)
+
+
 @pytest.mark.parametrize("case", sc.TAIL_CASES, ids=lambda c: c.name)
 def test_stage_parity_gemm_tail_pieces(case):
     """The pieces that the last, incomplete round of a prefill GEMM launch is cut into, on ragged rows and columns."""
